@@ -1,0 +1,138 @@
+/*
+ * emm.h -- C ABI of the MI355X (gfx950) prefix-cached paged prefill attention library.
+ *
+ * The library implements the attention hot path behind a unified multimodal prefix cache
+ * (ElasticMM, arXiv 2507.10069, Section 3.3): a request's leading tokens (image or video tokens
+ * plus shared text) already have their key/value entries in a paged KV pool (Appendix A), and
+ * prefill runs only over the remaining "new" tokens, reading the cached entries instead of
+ * recomputing them.  Appendix B.7 states what the result must be: identical to prefilling the
+ * whole sequence.  Three device operations are exported:
+ *
+ *   emm_kv_scatter    store the new tokens' K/V rows in their pool slots          (Section 2.2)
+ *   emm_prefill_attn  causal grouped-query attention of the new tokens over
+ *                     cached prefix + new tokens, read from the pool       (Section 3.3, App. B.7)
+ *   emm_cross_attn    unmasked attention of text queries over cached image K/V
+ *                     for encoder-decoder models                                  (Section 2.1)
+ *
+ * Conventions common to all calls
+ *   - Every pointer marked "device" is memory of the current HIP device, owned by the caller; the
+ *     library allocates and frees nothing and keeps no state between calls.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     return without waiting for it.  Errors are reported by return code only.
+ *   - Host-side checks cover the scalar fields, null pointers and 16-byte alignment of tensor
+ *     pointers.  Device-resident arrays (page table, lengths) are trusted; check host copies of
+ *     them with emm_validate_batch_host.
+ *   - Pool layout: [num_pages][num_kv_heads][page_size][head_dim], K and V in separate pools.
+ *     Logical token slot i of request r lives in page page_table[r][i / page_size] at offset
+ *     i % page_size.  Packed layouts: q, out [T][num_q_heads][head_dim]; k_new, v_new
+ *     [T][num_kv_heads][head_dim]; rows of request r are cu_new_lens[r] .. cu_new_lens[r+1]-1.
+ *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
+ *   - Element offsets are computed in 64 bits.
+ *   - Supported: page_size 16; EMM_BF16 with head_dim 128 (MFMA kernels); EMM_F32 with head_dim 64
+ *     or 128 (plain fp32 kernels).  Anything else returns EMM_ERR_UNSUPPORTED.
+ *   - A page that receives new tokens must be referenced by exactly one request: shared pages
+ *     (prefix-tree nodes with several users, Appendix A) are read-only.
+ */
+#ifndef EMM_H
+#define EMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EMM_OK = 0,
+    EMM_ERR_NULL = 1,          /* a required pointer is NULL                                   */
+    EMM_ERR_INVALID_ARG = 2,   /* a scalar field is out of range or a pointer is misaligned    */
+    EMM_ERR_UNSUPPORTED = 3,   /* valid request, but no kernel for this dtype/head_dim/page    */
+    EMM_ERR_WORKSPACE = 4,     /* workspace_bytes smaller than emm_prefill_attn_workspace_size */
+    EMM_ERR_LAUNCH = 5         /* the HIP runtime refused the launch                           */
+} emm_status;
+
+typedef enum { EMM_F32 = 0, EMM_BF16 = 1 } emm_dtype;
+
+/* One batch of requests.  Scalars are host values; the four arrays are device memory. */
+typedef struct {
+    int32_t num_reqs;            /* B >= 0                                                       */
+    int32_t num_q_heads;         /* H, a multiple of num_kv_heads                                */
+    int32_t num_kv_heads;        /* Hkv                                                          */
+    int32_t head_dim;            /* d                                                            */
+    int32_t page_size;           /* tokens per page ("block size")                               */
+    int32_t num_pages;           /* pages in each pool                                           */
+    int32_t max_pages_per_req;   /* row stride of page_table                                     */
+    int32_t total_new_tokens;    /* T = cu_new_lens[B]; known to the host so no sync is needed   */
+    int32_t max_new_len;         /* max_r new_lens[r]                                            */
+    int32_t dtype;               /* emm_dtype of q, k, v, out and both pools                     */
+    float softmax_scale;         /* scores are softmax_scale * <q, k>                            */
+    int32_t reserved;            /* must be 0                                                    */
+    const int32_t *page_table;   /* device [B][max_pages_per_req] physical page ids              */
+    const int32_t *prefix_lens;  /* device [B] tokens already valid in the pages                 */
+    const int32_t *new_lens;     /* device [B] new tokens = query rows of the request            */
+    const int32_t *cu_new_lens;  /* device [B+1] exclusive prefix sum of new_lens                */
+} emm_batch;
+
+/*
+ * KV scatter (Section 2.2: prefill produces the KV cache of all input tokens; Appendix B.5's
+ * exact-copy requirement).  For request r, new token j, KV head h: copy the head_dim elements of
+ * k_new[cu_new_lens[r]+j][h] bit for bit to slot prefix_lens[r]+j of request r in k_cache; the same
+ * for v_new / v_cache.  No other byte of the pools is written.
+ *   k_new, v_new      device, read,  [T][Hkv][d]
+ *   k_cache, v_cache  device, write, [num_pages][Hkv][page_size][d]
+ * T == 0 is a no-op.
+ */
+emm_status emm_kv_scatter(const emm_batch *batch, const void *k_new, const void *v_new,
+                          void *k_cache, void *v_cache, void *hip_stream);
+
+/* Bytes of device workspace emm_prefill_attn / emm_cross_attn need for this batch (may be 0).
+ * Host-only; reads only the scalar fields. */
+emm_status emm_prefill_attn_workspace_size(const emm_batch *batch, size_t *bytes);
+
+/*
+ * Prefix-cached causal prefill attention (Section 3.3; Appendix B.7, g_P^remaining).
+ * Query row j of request r attends to the request's logical slots 0 .. prefix_lens[r]+j, i.e. to
+ * the whole cached prefix and to the new tokens up to and including itself; the new tokens' K/V
+ * are read from the pool, so emm_kv_scatter must precede this call on the same stream.
+ *   q       device, read,  [T][H][d]
+ *   out     device, write, [T][H][d], same dtype as q (bf16 rounded to nearest even)
+ *   lse     device, write, [T][H] fp32 natural-log softmax denominators, or NULL
+ *   workspace  device scratch of at least emm_prefill_attn_workspace_size bytes (may be NULL if 0)
+ * bf16 path: scores and both products accumulate in fp32, softmax weights are rounded to bf16 for
+ * the value product.  Results are run-to-run bitwise deterministic.
+ */
+emm_status emm_prefill_attn(const emm_batch *batch, const void *q, const void *k_cache,
+                            const void *v_cache, void *out, float *lse, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Cross-attention variant (Section 2.1: in encoder-decoder MLLMs text tokens meet vision tokens
+ * only in cross-attention layers).  Every query row of request r attends, without mask, to slots
+ * 0 .. prefix_lens[r]-1 (the cached image K/V).  new_lens[r] is the number of queries.  A request
+ * with prefix_lens[r] == 0 (text-only request in the batch) gets zero rows and lse = -inf.
+ * Arguments as for emm_prefill_attn; the pools are only read.
+ */
+emm_status emm_cross_attn(const emm_batch *batch, const void *q, const void *k_cache,
+                          const void *v_cache, void *out, float *lse, void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Host-side consistency check of a batch whose arrays are given as HOST copies (debug / tests).
+ * `causal` != 0 checks the prefill contract (pages of prefix+new tokens valid, pages that receive
+ * new tokens referenced once), 0 checks the cross-attention contract (pages of the prefix valid).
+ * Only the scalar fields of `batch` are read.  Returns EMM_OK or EMM_ERR_INVALID_ARG.
+ */
+emm_status emm_validate_batch_host(const emm_batch *batch, const int32_t *host_page_table,
+                                   const int32_t *host_prefix_lens, const int32_t *host_new_lens,
+                                   const int32_t *host_cu_new_lens, int causal);
+
+const char *emm_status_string(emm_status status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int emm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMM_H */

@@ -1,0 +1,202 @@
+"""ctypes binding of the C-ABI library declared in ``include/emm.h``.
+
+Argument marshalling only: every function has the name and the meaning of the C entry point it
+calls, takes torch tensors that live on the GPU (PyTorch is used for device memory and streams,
+nothing else), and raises :class:`EmmError` on a non-zero status.  There is no fallback: if
+``libemm.so`` has not been built, loading fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libemm.so")
+
+EMM_OK, EMM_ERR_NULL, EMM_ERR_INVALID_ARG, EMM_ERR_UNSUPPORTED, EMM_ERR_WORKSPACE, EMM_ERR_LAUNCH = range(6)
+EMM_F32, EMM_BF16 = 0, 1
+
+EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn",
+           "emm_validate_batch_host", "emm_status_string", "emm_version"]
+
+
+class EmmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (where, emm_status_string(status), status))
+
+
+class emm_batch(ctypes.Structure):
+    _fields_ = [("num_reqs", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+                ("max_pages_per_req", ctypes.c_int32), ("total_new_tokens", ctypes.c_int32),
+                ("max_new_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("reserved", ctypes.c_int32), ("page_table", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
+                ("new_lens", ctypes.c_void_p), ("cu_new_lens", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load ``libemm.so`` (built by ``python -m paper_2507_10069_amd.build``) and declare signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build the HIP library first (python -m paper_2507_10069_amd.build, or "
+            "__graft_entry__.build()).  There is no CPU fallback." % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    bp, vp, i32p = ctypes.POINTER(emm_batch), ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
+    lib.emm_kv_scatter.restype = ctypes.c_int
+    lib.emm_kv_scatter.argtypes = [bp, vp, vp, vp, vp, vp]
+    lib.emm_prefill_attn_workspace_size.restype = ctypes.c_int
+    lib.emm_prefill_attn_workspace_size.argtypes = [bp, ctypes.POINTER(ctypes.c_size_t)]
+    for name in ("emm_prefill_attn", "emm_cross_attn"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.emm_validate_batch_host.restype = ctypes.c_int
+    lib.emm_validate_batch_host.argtypes = [bp, i32p, i32p, i32p, i32p, ctypes.c_int]
+    lib.emm_status_string.restype = ctypes.c_char_p
+    lib.emm_status_string.argtypes = [ctypes.c_int]
+    lib.emm_version.restype = ctypes.c_int
+    lib.emm_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    return int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    handle = int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+    return handle or None
+
+
+def make_batch(*, num_reqs, num_q_heads, num_kv_heads, head_dim, page_size, num_pages, max_pages_per_req,
+               total_new_tokens, max_new_len, dtype, softmax_scale, page_table=None, prefix_lens=None,
+               new_lens=None, cu_new_lens=None) -> emm_batch:
+    """Fill the descriptor; the four arrays are int32 device tensors (or None for host-only calls)."""
+    code = {"f32": EMM_F32, "bf16": EMM_BF16}.get(dtype, dtype)
+    return emm_batch(num_reqs, num_q_heads, num_kv_heads, head_dim, page_size, num_pages, max_pages_per_req,
+                     total_new_tokens, max_new_len, code, float(softmax_scale), 0,
+                     _ptr(page_table), _ptr(prefix_lens), _ptr(new_lens), _ptr(cu_new_lens))
+
+
+def _check(status: int, where: str) -> None:
+    if status != EMM_OK:
+        raise EmmError(status, where)
+
+
+def emm_status_string(status: int) -> str:
+    return load().emm_status_string(int(status)).decode()
+
+
+def emm_version() -> int:
+    return int(load().emm_version())
+
+
+def emm_kv_scatter(batch: emm_batch, k_new, v_new, k_cache, v_cache, stream=None) -> None:
+    _check(load().emm_kv_scatter(ctypes.byref(batch), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                 _stream(stream)), "emm_kv_scatter")
+
+
+def emm_prefill_attn_workspace_size(batch: emm_batch) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().emm_prefill_attn_workspace_size(ctypes.byref(batch), ctypes.byref(n)),
+           "emm_prefill_attn_workspace_size")
+    return int(n.value)
+
+
+def _attn(name: str, batch, q, k_cache, v_cache, out, lse, workspace, stream) -> None:
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    _check(getattr(load(), name)(ctypes.byref(batch), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out),
+                                 _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)), name)
+
+
+def emm_prefill_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, workspace=None, stream=None) -> None:
+    _attn("emm_prefill_attn", batch, q, k_cache, v_cache, out, lse, workspace, stream)
+
+
+def emm_cross_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, workspace=None, stream=None) -> None:
+    _attn("emm_cross_attn", batch, q, k_cache, v_cache, out, lse, workspace, stream)
+
+
+def emm_validate_batch_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray,
+                            new_lens: np.ndarray, cu_new_lens: np.ndarray, causal: bool) -> int:
+    """Returns the status instead of raising: it is a checker."""
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (page_table, prefix_lens, new_lens, cu_new_lens)]
+    return int(load().emm_validate_batch_host(ctypes.byref(batch), *[a.ctypes.data_as(i32p) for a in arrs],
+                                              1 if causal else 0))
+
+
+# ---------------------------------------------------------------------------------------------
+# Moving a host workload (paper_2507_10069_amd.workloads.Workload) to the device.
+# ---------------------------------------------------------------------------------------------
+class DeviceWorkload:
+    """Device copies of a workload's tensors plus the filled descriptor."""
+
+    def __init__(self, wl, device="cuda:0"):
+        import torch
+        self.wl = wl
+        self.device = torch.device(device)
+
+        def dev(a):
+            if a is None:
+                return None
+            if a.dtype == np.uint16:
+                return torch.from_numpy(a.view(np.int16)).to(self.device).view(torch.bfloat16)
+            return torch.from_numpy(a).to(self.device)
+
+        self.page_table = dev(wl.page_table)
+        self.prefix_lens = dev(wl.prefix_lens)
+        self.new_lens = dev(wl.new_lens)
+        self.cu_new_lens = dev(wl.cu_new_lens)
+        self.q = dev(wl.q)
+        self.k_new = dev(wl.k_new)
+        self.v_new = dev(wl.v_new)
+        self.k_cache = dev(wl.k_cache)
+        self.v_cache = dev(wl.v_cache)
+        self.out = torch.empty_like(self.q)
+        self.lse = torch.empty((wl.total_new_tokens, wl.num_q_heads), dtype=torch.float32, device=self.device)
+        self.batch = make_batch(num_reqs=wl.num_reqs, num_q_heads=wl.num_q_heads, num_kv_heads=wl.num_kv_heads,
+                                head_dim=wl.head_dim, page_size=wl.page_size, num_pages=wl.num_pages,
+                                max_pages_per_req=wl.max_pages_per_req, total_new_tokens=wl.total_new_tokens,
+                                max_new_len=wl.max_new_len, dtype=wl.dtype, softmax_scale=wl.softmax_scale,
+                                page_table=self.page_table, prefix_lens=self.prefix_lens,
+                                new_lens=self.new_lens, cu_new_lens=self.cu_new_lens)
+        ws = emm_prefill_attn_workspace_size(self.batch)
+        self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=self.device) if ws else None
+
+    def scatter(self, stream=None) -> None:
+        if self.wl.kind == "causal":
+            emm_kv_scatter(self.batch, self.k_new, self.v_new, self.k_cache, self.v_cache, stream)
+
+    def attention(self, stream=None) -> None:
+        fn = emm_prefill_attn if self.wl.kind == "causal" else emm_cross_attn
+        fn(self.batch, self.q, self.k_cache, self.v_cache, self.out, self.lse, self.workspace, stream)
+
+    def step(self, stream=None) -> None:
+        """One pass of the hot path: scatter the new K/V, then attention."""
+        self.scatter(stream)
+        self.attention(stream)
+
+    @staticmethod
+    def to_numpy_bits(t) -> np.ndarray:
+        """Device tensor -> host numpy array in the workload's storage form."""
+        import torch
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy()

@@ -1,0 +1,207 @@
+// C ABI of the library: host-side validation and dispatch to the kernels.  See include/emm.h for the
+// contract of every entry point.  All checks that can fail run before the first HIP call, so the
+// error paths work on a machine without a GPU.
+#include "../../include/emm.h"
+#include "emm_internal.h"
+
+#include <cmath>
+#include <vector>
+
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+emm_status check_scalars(const emm_batch* b)
+{
+    if (b == nullptr) return EMM_ERR_NULL;
+    if (b->num_reqs < 0 || b->num_q_heads <= 0 || b->num_kv_heads <= 0 || b->head_dim <= 0 ||
+        b->page_size <= 0 || b->num_pages < 0 || b->max_pages_per_req < 0 || b->total_new_tokens < 0 ||
+        b->max_new_len < 0 || b->max_new_len > b->total_new_tokens || b->reserved != 0)
+        return EMM_ERR_INVALID_ARG;
+    if (b->num_q_heads % b->num_kv_heads != 0) return EMM_ERR_INVALID_ARG;
+    if (b->dtype != EMM_F32 && b->dtype != EMM_BF16) return EMM_ERR_INVALID_ARG;
+    if (!(b->softmax_scale > 0.0f) || !std::isfinite(b->softmax_scale)) return EMM_ERR_INVALID_ARG;
+    if (b->num_reqs > 0 && b->total_new_tokens > 0 && b->max_new_len == 0) return EMM_ERR_INVALID_ARG;
+    return EMM_OK;
+}
+
+emm_status check_supported(const emm_batch* b)
+{
+    if (b->page_size != 16) return EMM_ERR_UNSUPPORTED;
+    if (b->dtype == EMM_BF16 && b->head_dim != 128) return EMM_ERR_UNSUPPORTED;
+    if (b->dtype == EMM_F32 && b->head_dim != 64 && b->head_dim != 128) return EMM_ERR_UNSUPPORTED;
+    return EMM_OK;
+}
+
+emm_status check_arrays(const emm_batch* b)
+{
+    if (b->num_reqs == 0) return EMM_OK;
+    if (b->page_table == nullptr || b->prefix_lens == nullptr || b->new_lens == nullptr ||
+        b->cu_new_lens == nullptr)
+        return EMM_ERR_NULL;
+    return EMM_OK;
+}
+
+emm::BatchView view_of(const emm_batch* b)
+{
+    emm::BatchView v;
+    v.page_table = b->page_table;
+    v.prefix_lens = b->prefix_lens;
+    v.new_lens = b->new_lens;
+    v.cu_new_lens = b->cu_new_lens;
+    v.num_reqs = b->num_reqs;
+    v.num_q_heads = b->num_q_heads;
+    v.num_kv_heads = b->num_kv_heads;
+    v.head_dim = b->head_dim;
+    v.page_size = b->page_size;
+    v.num_pages = b->num_pages;
+    v.max_pages = b->max_pages_per_req;
+    v.total_new_tokens = b->total_new_tokens;
+    v.max_new_len = b->max_new_len;
+    v.softmax_scale = b->softmax_scale;
+    return v;
+}
+
+emm_status attention(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache, void* out,
+                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, int causal)
+{
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    st = check_supported(b);
+    if (st != EMM_OK) return st;
+    size_t need = 0;
+    st = emm_prefill_attn_workspace_size(b, &need);
+    if (st != EMM_OK) return st;
+    if (b->num_reqs == 0 || b->total_new_tokens == 0) return EMM_OK;
+    st = check_arrays(b);
+    if (st != EMM_OK) return st;
+    if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr) return EMM_ERR_NULL;
+    if (need > 0 && workspace == nullptr) return EMM_ERR_NULL;
+    if (workspace_bytes < need) return EMM_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+        (lse != nullptr && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) ||
+        (workspace != nullptr && !aligned16(workspace)))
+        return EMM_ERR_INVALID_ARG;
+    if (b->num_pages == 0 || b->max_pages_per_req == 0) return EMM_ERR_INVALID_ARG;
+
+    emm::AttnArgs args;
+    args.b = view_of(b);
+    args.q = q;
+    args.k_cache = k_cache;
+    args.v_cache = v_cache;
+    args.out = out;
+    args.lse = lse;
+    args.causal = causal;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const hipError_t err = (b->dtype == EMM_BF16) ? emm::launch_attn_bf16_d128(args, stream)
+                                                  : emm::launch_attn_f32(args, stream);
+    return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+emm_status emm_kv_scatter(const emm_batch* b, const void* k_new, const void* v_new, void* k_cache,
+                          void* v_cache, void* hip_stream)
+{
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    st = check_supported(b);
+    if (st != EMM_OK) return st;
+    if (b->num_reqs == 0 || b->total_new_tokens == 0) return EMM_OK;
+    st = check_arrays(b);
+    if (st != EMM_OK) return st;
+    if (k_new == nullptr || v_new == nullptr || k_cache == nullptr || v_cache == nullptr) return EMM_ERR_NULL;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+        return EMM_ERR_INVALID_ARG;
+    if (b->num_pages == 0 || b->max_pages_per_req == 0) return EMM_ERR_INVALID_ARG;
+    const int elt = (b->dtype == EMM_BF16) ? 2 : 4;
+    const hipError_t err = emm::launch_kv_scatter(view_of(b), k_new, v_new, k_cache, v_cache, elt,
+                                                  static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
+}
+
+emm_status emm_prefill_attn_workspace_size(const emm_batch* b, size_t* bytes)
+{
+    if (bytes == nullptr) return EMM_ERR_NULL;
+    *bytes = 0;
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    return check_supported(b);
+}
+
+emm_status emm_prefill_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,
+                            void* out, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1);
+}
+
+emm_status emm_cross_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,
+                          void* out, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 0);
+}
+
+emm_status emm_validate_batch_host(const emm_batch* b, const int32_t* pt, const int32_t* prefix,
+                                   const int32_t* new_lens, const int32_t* cu, int causal)
+{
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    if (b->num_reqs == 0) return EMM_OK;
+    if (pt == nullptr || prefix == nullptr || new_lens == nullptr || cu == nullptr) return EMM_ERR_NULL;
+    if (cu[0] != 0) return EMM_ERR_INVALID_ARG;
+    std::vector<int32_t> writers(static_cast<size_t>(b->num_pages), 0);
+    int32_t max_new = 0;
+    for (int r = 0; r < b->num_reqs; ++r) {
+        if (prefix[r] < 0 || new_lens[r] < 0) return EMM_ERR_INVALID_ARG;
+        if (cu[r + 1] - cu[r] != new_lens[r]) return EMM_ERR_INVALID_ARG;
+        if (new_lens[r] > max_new) max_new = new_lens[r];
+        const int64_t ctx = static_cast<int64_t>(prefix[r]) + (causal ? new_lens[r] : 0);
+        const int64_t pages = (ctx + b->page_size - 1) / b->page_size;
+        if (pages > b->max_pages_per_req) return EMM_ERR_INVALID_ARG;
+        for (int64_t lp = 0; lp < pages; ++lp) {
+            const int32_t pg = pt[static_cast<int64_t>(r) * b->max_pages_per_req + lp];
+            if (pg < 0 || pg >= b->num_pages) return EMM_ERR_INVALID_ARG;
+        }
+        if (causal && new_lens[r] > 0) {
+            // pages that receive new tokens: written by this request, so no one else may reference them
+            for (int64_t lp = prefix[r] / b->page_size; lp < pages; ++lp)
+                writers[static_cast<size_t>(pt[static_cast<int64_t>(r) * b->max_pages_per_req + lp])] += 1;
+        }
+    }
+    if (cu[b->num_reqs] != b->total_new_tokens || max_new != b->max_new_len) return EMM_ERR_INVALID_ARG;
+    if (causal) {
+        // a written page may be referenced only by its writer
+        std::vector<int32_t> refs(static_cast<size_t>(b->num_pages), 0);
+        for (int r = 0; r < b->num_reqs; ++r) {
+            const int64_t ctx = static_cast<int64_t>(prefix[r]) + new_lens[r];
+            const int64_t pages = (ctx + b->page_size - 1) / b->page_size;
+            for (int64_t lp = 0; lp < pages; ++lp)
+                refs[static_cast<size_t>(pt[static_cast<int64_t>(r) * b->max_pages_per_req + lp])] += 1;
+        }
+        for (int32_t pg = 0; pg < b->num_pages; ++pg)
+            if (writers[static_cast<size_t>(pg)] > 0 && refs[static_cast<size_t>(pg)] != 1)
+                return EMM_ERR_INVALID_ARG;
+    }
+    return EMM_OK;
+}
+
+const char* emm_status_string(emm_status s)
+{
+    switch (s) {
+        case EMM_OK: return "ok";
+        case EMM_ERR_NULL: return "required pointer is null";
+        case EMM_ERR_INVALID_ARG: return "invalid argument";
+        case EMM_ERR_UNSUPPORTED: return "unsupported dtype / head_dim / page_size";
+        case EMM_ERR_WORKSPACE: return "workspace too small";
+        case EMM_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+int emm_version(void) { return kVersion; }
+
+}  // extern "C"

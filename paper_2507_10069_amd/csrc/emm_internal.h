@@ -1,0 +1,37 @@
+// Internal declarations shared by the translation units of the HIP library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace emm {
+
+// Everything a device kernel needs to know about a batch (a by-value copy of the public
+// descriptor plus tensor pointers).
+struct BatchView {
+    const int32_t* page_table;   // [B][max_pages]
+    const int32_t* prefix_lens;  // [B]
+    const int32_t* new_lens;     // [B]
+    const int32_t* cu_new_lens;  // [B+1]
+    int32_t num_reqs, num_q_heads, num_kv_heads, head_dim;
+    int32_t page_size, num_pages, max_pages, total_new_tokens, max_new_len;
+    float softmax_scale;
+};
+
+struct AttnArgs {
+    BatchView b;
+    const void* q;        // [T][H][d]
+    const void* k_cache;  // [num_pages][Hkv][16][d]
+    const void* v_cache;
+    void* out;            // [T][H][d]
+    float* lse;           // [T][H] or nullptr
+    int32_t causal;       // 1: keys 0..P+j ; 0: keys 0..P-1
+};
+
+// Each launcher enqueues on `stream` and returns the launch status.
+hipError_t launch_kv_scatter(const BatchView& b, const void* k_new, const void* v_new, void* k_cache,
+                             void* v_cache, int elt_bytes, hipStream_t stream);
+hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
+hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace emm

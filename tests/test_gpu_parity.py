@@ -1,0 +1,214 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle on the same seeded inputs.
+
+Bars: the KV scatter is bit-exact over the whole pool; bf16 attention outputs are within max-abs 2e-2
+and mean-abs 2e-3 of the oracle (bf16 inputs, fp32 accumulation); the fp32 configuration is held to
+max-abs 1e-4.  Sizes the oracle finishes in seconds are compared element by element; the full-size
+workloads are compared on sampled query tokens (all heads, all channels)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import as_f64, err_stats
+from paper_2507_10069_amd import binding as B
+from paper_2507_10069_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+BF16_MAX_ABS, BF16_MEAN_ABS = 2e-2, 2e-3
+F32_MAX_ABS = 1e-4
+LSE_ABS = 2e-3
+
+
+def _gpu_run(wl, poison_unused=False):
+    dw = B.DeviceWorkload(wl)
+    dw.out.zero_()
+    dw.step()
+    torch.cuda.synchronize()
+    return dw
+
+
+def _compare(wl, dw, tokens=None):
+    kc, vc, out_ref, lse_ref = oracle.run_workload(wl, tokens)
+    if wl.kind == "causal":
+        assert B.DeviceWorkload.to_numpy_bits(dw.k_cache).tobytes() == kc.tobytes(), "K pool differs"
+        assert B.DeviceWorkload.to_numpy_bits(dw.v_cache).tobytes() == vc.tobytes(), "V pool differs"
+    out = as_f64(B.DeviceWorkload.to_numpy_bits(dw.out))
+    lse = dw.lse.cpu().numpy().astype(np.float64)
+    if tokens is not None:
+        out, lse = out[np.asarray(tokens)], lse[np.asarray(tokens)]
+    assert np.isfinite(out).all()
+    mx, mean = err_stats(out, out_ref)
+    finite = np.isfinite(lse_ref)
+    lse_err = float(np.abs(lse[finite] - lse_ref[finite]).max()) if finite.any() else 0.0
+    assert (np.isneginf(lse[~finite])).all()
+    if wl.dtype == "bf16":
+        assert mx <= BF16_MAX_ABS and mean <= BF16_MEAN_ABS, (mx, mean)
+    else:
+        assert mx <= F32_MAX_ABS, mx
+    assert lse_err <= LSE_ABS, lse_err
+    return mx, mean, lse_err
+
+
+def _sample_tokens(wl, n, seed=0):
+    """Sampled packed tokens: first and last row of every request (diagonal edges) plus random ones."""
+    rng = np.random.default_rng(seed)
+    cu = wl.cu_new_lens
+    picks = set()
+    for r in range(wl.num_reqs):
+        if wl.new_lens[r] > 0:
+            picks.update([int(cu[r]), int(cu[r + 1]) - 1])
+    picks.update(int(t) for t in rng.integers(0, wl.total_new_tokens, size=n))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(1, 1), (2, 4), (3, 16), (4, 8), (5, 8), (2, 1)])
+def test_elementwise_parity(cfg, shrink):
+    print("case cfg=%d shrink=%d" % (cfg, shrink), flush=True)
+    wl = W.config(cfg, shrink)
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+
+
+@pytest.mark.parametrize("cfg,n", [(3, 24), (4, 96), (5, 48)])
+def test_full_size_sampled_parity(cfg, n):
+    """The sizes and launch configuration bench.py times."""
+    print("case full cfg=%d" % cfg, flush=True)
+    wl = W.config(cfg, 1)
+    dw = _gpu_run(wl)
+    tokens = _sample_tokens(wl, n, seed=cfg)
+    print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
+
+
+RAGGED = [(0, 1), (0, 2), (0, 33), (1, 1), (15, 31), (16, 32), (17, 33), (63, 127), (64, 128), (65, 129),
+          (200, 300), (0, 129), (127, 1), (128, 64), (1000, 7)]
+
+
+def test_ragged_causal_sweep():
+    """Prefix / new-token lengths around every tile boundary (16-token pages, 64-key tiles, 32-row waves,
+    128-row workgroups), several requests per batch, including an empty request."""
+    for gi, (H, Hkv) in enumerate(((8, 2), (7, 1), (4, 4))):
+        prefix = [p for p, _ in RAGGED] + [40]
+        new = [n for _, n in RAGGED] + [0]
+        print("case ragged heads=%d/%d" % (H, Hkv), flush=True)
+        wl = W.build_workload("ragged", "causal", "bf16", 500 + gi, num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                              page_size=16, prefix_lens=prefix, new_lens=new)
+        dw = _gpu_run(wl)
+        _compare(wl, dw)
+
+
+def test_ragged_cross_sweep():
+    """Cross-attention: cached lengths around page and tile boundaries, and a request with nothing cached
+    (zero rows, lse = -inf)."""
+    lkv = [0, 1, 4, 15, 16, 17, 63, 64, 65, 100, 127, 128, 129, 1601]
+    nq = [5, 1, 33, 32, 31, 128, 129, 7, 64, 2, 200, 1, 130, 45]
+    print("case ragged cross", flush=True)
+    wl = W.build_workload("ragged_cross", "cross", "bf16", 600, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                          page_size=16, prefix_lens=lkv, new_lens=nq)
+    dw = _gpu_run(wl)
+    _compare(wl, dw)
+    out = B.DeviceWorkload.to_numpy_bits(dw.out)
+    assert (out[:5] == 0).all()
+
+
+def test_f32_head_dim_128_and_cross():
+    print("case f32 d=128 causal + cross", flush=True)
+    wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
+                          page_size=16, prefix_lens=[33, 0, 70], new_lens=[17, 65, 1])
+    _compare(wl, _gpu_run(wl))
+    wl = W.build_workload("f32_cross", "cross", "f32", 701, num_q_heads=4, num_kv_heads=1, head_dim=64,
+                          page_size=16, prefix_lens=[0, 70, 16], new_lens=[3, 9, 66])
+    _compare(wl, _gpu_run(wl))
+
+
+def test_garbage_in_unused_slots_is_ignored():
+    """Slots past a request's tokens (tail of the last page) and unreferenced pages may hold anything,
+    including NaN and Inf bit patterns; results must not change."""
+    print("case garbage slots", flush=True)
+    wl = W.build_workload("garbage", "causal", "bf16", 800, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                          page_size=16, prefix_lens=[37, 0, 64], new_lens=[70, 5, 130])
+    ref = _gpu_run(wl)
+    ref_out = B.DeviceWorkload.to_numpy_bits(ref.out)
+    for pattern in (0x7FC0, 0x7F80, 0xFF80):            # NaN, +Inf, -Inf
+        wl2 = W.build_workload("garbage", "causal", "bf16", 800, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                               page_size=16, prefix_lens=[37, 0, 64], new_lens=[70, 5, 130])
+        for pool in (wl2.k_cache, wl2.v_cache):
+            pool[pool == W.SENTINEL_BF16_BITS] = pattern
+        dw = _gpu_run(wl2)
+        assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == ref_out.tobytes(), hex(pattern)
+    wl3 = W.build_workload("garbage_x", "cross", "bf16", 801, num_q_heads=8, num_kv_heads=2, head_dim=128,
+                           page_size=16, prefix_lens=[37, 100], new_lens=[40, 3])
+    ref = B.DeviceWorkload.to_numpy_bits(_gpu_run(wl3).out)
+    for pool in (wl3.k_cache, wl3.v_cache):
+        pool[pool == W.SENTINEL_BF16_BITS] = 0x7FC0
+    assert B.DeviceWorkload.to_numpy_bits(_gpu_run(wl3).out).tobytes() == ref.tobytes()
+
+
+def test_scatter_bit_exact_with_arbitrary_bit_patterns():
+    """The scatter moves bytes: NaN payloads, denormals and negative zeros survive unchanged."""
+    print("case scatter bit patterns", flush=True)
+    for dtype, cfg in (("bf16", 2), ("f32", 1)):
+        wl = W.config(cfg, 4)
+        rng = np.random.default_rng(900)
+        bits = rng.integers(0, 2 ** 16, size=wl.k_new.shape, dtype=np.uint16) if dtype == "bf16" else None
+        if dtype == "bf16":
+            wl.k_new = bits
+            wl.v_new = rng.integers(0, 2 ** 16, size=wl.v_new.shape, dtype=np.uint16)
+        else:
+            wl.k_new = rng.integers(0, 2 ** 32, size=wl.k_new.shape, dtype=np.uint32).view(np.float32)
+            wl.v_new = rng.integers(0, 2 ** 32, size=wl.v_new.shape, dtype=np.uint32).view(np.float32)
+        dw = B.DeviceWorkload(wl)
+        dw.scatter()
+        torch.cuda.synchronize()
+        kc, vc = oracle.kv_scatter(wl.page_table, wl.prefix_lens, wl.new_lens, wl.cu_new_lens, wl.k_new,
+                                   wl.v_new, wl.k_cache, wl.v_cache)
+        if dtype == "bf16":
+            got_k, got_v = B.DeviceWorkload.to_numpy_bits(dw.k_cache), B.DeviceWorkload.to_numpy_bits(dw.v_cache)
+        else:
+            got_k, got_v = dw.k_cache.cpu().numpy(), dw.v_cache.cpu().numpy()
+        assert got_k.tobytes() == kc.tobytes() and got_v.tobytes() == vc.tobytes()
+
+
+@pytest.mark.parametrize("cfg,shrink", [(1, 1), (2, 4), (5, 8)])
+def test_page_permutation_invariance_bitwise(cfg, shrink):
+    """Relabelling physical pages (pool and table together) must not change a single output bit."""
+    print("case permutation cfg=%d" % cfg, flush=True)
+    wl = W.config(cfg, shrink)
+    out = B.DeviceWorkload.to_numpy_bits(_gpu_run(wl).out)
+    perm = np.random.default_rng(5).permutation(wl.num_pages)
+    wl2 = W.config(cfg, shrink)
+    wl2.k_cache = np.empty_like(wl.k_cache)
+    wl2.v_cache = np.empty_like(wl.v_cache)
+    wl2.k_cache[perm] = wl.k_cache
+    wl2.v_cache[perm] = wl.v_cache
+    wl2.page_table = np.where(wl.page_table >= 0, perm[np.maximum(wl.page_table, 0)], -1).astype(np.int32)
+    out2 = B.DeviceWorkload.to_numpy_bits(_gpu_run(wl2).out)
+    assert out.tobytes() == out2.tobytes()
+
+
+def test_run_to_run_determinism_and_constant_v():
+    print("case determinism", flush=True)
+    wl = W.config(4, 8)
+    a = _gpu_run(wl)
+    b = _gpu_run(wl)
+    assert B.DeviceWorkload.to_numpy_bits(a.out).tobytes() == B.DeviceWorkload.to_numpy_bits(b.out).tobytes()
+    assert a.lse.cpu().numpy().tobytes() == b.lse.cpu().numpy().tobytes()
+    # V == 1 everywhere the request has tokens: the output is the sum of the softmax weights
+    wl.v_cache[wl.v_cache != W.SENTINEL_BF16_BITS] = 0x3F80
+    wl.v_new[...] = 0x3F80
+    out = as_f64(B.DeviceWorkload.to_numpy_bits(_gpu_run(wl).out))
+    assert np.abs(out - 1.0).max() <= 8e-3
+
+
+def test_error_codes_on_device():
+    """Status codes through the binding with real device tensors."""
+    wl = W.config(1, 1)
+    dw = B.DeviceWorkload(wl)
+    with pytest.raises(B.EmmError) as e:
+        B.emm_prefill_attn(dw.batch, dw.q, dw.k_cache, dw.v_cache, None)
+    assert e.value.status == B.EMM_ERR_NULL
+    bad = B.DeviceWorkload(wl)
+    bad.batch.page_size = 8
+    with pytest.raises(B.EmmError) as e:
+        bad.scatter()
+    assert e.value.status == B.EMM_ERR_UNSUPPORTED
