@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-cached paged prefill hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: KV scatter of the new tokens,
+then prefix-cached causal attention (both through the C ABI, inputs already resident in HBM).  The
+timed workload is the long video-prefix prefill (2 requests x [16384 cached + 2048 new tokens],
+28 query / 4 KV heads, head_dim 128, page size 16, bf16), the configuration the throughput target
+is stated on.  One JSON line is printed on stdout; everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz (published dense bf16 figure, 2.5 PF)
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_workload(dw, steps, warmup):
+    """Returns (ms per step, mean attention-kernel ms, mean scatter-kernel ms) from HIP events recorded
+    on the stream the kernels are launched on (torch's current stream)."""
+    import torch
+    for _ in range(warmup):
+        dw.step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i][0].record()
+        dw.scatter()
+        ev[i][1].record()
+        dw.attention()
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    scat = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    attn = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    dev_ms = ev[0][0].elapsed_time(ev[-1][2]) / steps
+    return max(wall_ms, dev_ms), attn, scat
+
+
+def cpu_baseline(wl, target_tokens):
+    """The fp64 oracle, as it stands, on an evenly spaced sample of the workload's query tokens."""
+    import numpy as np
+    import oracle
+    T = wl.total_new_tokens
+    tokens = np.unique(np.linspace(0, T - 1, num=min(T, target_tokens)).astype(np.int64))
+    kc, vc = oracle.kv_scatter(wl.page_table, wl.prefix_lens, wl.new_lens, wl.cu_new_lens, wl.k_new, wl.v_new,
+                               wl.k_cache, wl.v_cache)
+    t0 = time.perf_counter()
+    oracle.attention(wl.kind, wl.page_table, wl.prefix_lens, wl.new_lens, wl.cu_new_lens, wl.q, kc, vc,
+                     wl.softmax_scale, tokens)
+    dt = time.perf_counter() - t0
+    # algorithmic flops of exactly the sampled rows
+    cu = wl.cu_new_lens
+    flops = 0
+    for t in tokens.tolist():
+        r = int(np.searchsorted(cu, t, side="right") - 1)
+        flops += 4 * wl.head_dim * wl.num_q_heads * (int(wl.prefix_lens[r]) + (t - int(cu[r])) + 1)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d of %d query tokens evenly spaced (all %d heads), %.1f s of fp64 oracle time, "
+                      "%.3g tokens/s" % (len(tokens), T, wl.num_q_heads, dt, len(tokens) / dt),
+            "new_tokens_per_s": len(tokens) / dt}
+
+
+def read_traffic():
+    """HBM bytes per attention launch measured with rocprofv3 --pmc (see profiles/), if recorded."""
+    path = os.path.join(ROOT, "profiles", "attn_bf16_cfg3_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=3, help="named workload 1..5 (default 3, the target)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--others", action="store_true", help="also time the other named workloads (stderr + JSON)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between requests); "
+                 "run with --gpus 1")
+
+    import torch
+    from paper_2507_10069_amd import binding as B
+    from paper_2507_10069_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.load()                                            # fails loudly if libemm.so has not been built
+    torch.cuda.set_device(0)
+
+    wl = W.config(args.workload)
+    dw = B.DeviceWorkload(wl)
+    ms, attn_ms, scat_ms = time_workload(dw, args.steps, args.warmup)
+    flops = wl.attention_flops()
+    T = wl.total_new_tokens
+    tflops = flops / (ms * 1e-3) / 1e12
+    attn_tflops = flops / (attn_ms * 1e-3) / 1e12
+    log("workload %s: %.4f ms/step (attention %.4f ms, scatter %.4f ms), %.1f TFLOP/s whole step, "
+        "%.1f TFLOP/s attention kernel" % (wl.name, ms, attn_ms, scat_ms, tflops, attn_tflops))
+
+    result = {
+        "metric": "prefill_attention_tflops", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d requests, %d cached + %d new tokens each, %d/%d heads, head_dim %d, "
+                               "page %d, causal, KV scatter + attention per step"
+                               % (wl.name, wl.num_reqs, int(wl.prefix_lens[0]), int(wl.new_lens[0]),
+                                  wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size)
+                   if args.workload == 3 else wl.name,
+                   "total_new_tokens": T, "algorithmic_flops_per_step": flops, "parallelism": "single-gpu"},
+        "new_tokens_per_s": T / (ms * 1e-3),
+        "pct_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
+        "attention_ms": attn_ms, "scatter_ms": scat_ms,
+        "scatter_gbs": (wl.scatter_bytes() / (scat_ms * 1e-3) / 1e9) if scat_ms > 0 else None,
+        "roofline": {"bound": "mfma", "achieved": attn_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": read_traffic(),
+                     "kernel": "attn_bf16_d128_kernel"},
+    }
+    if args.others:
+        others = {}
+        for i in (1, 2, 4, 5):
+            w = W.config(i)
+            d = B.DeviceWorkload(w)
+            m, am, sm = time_workload(d, 30, 5)
+            others[w.name] = {"ms_per_step": m, "attention_ms": am, "scatter_ms": sm,
+                              "tflops": w.attention_flops() / (m * 1e-3) / 1e12,
+                              "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
+            log("workload %s: %s" % (w.name, others[w.name]))
+            del d
+        result["other_workloads"] = others
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_tokens)
+        log("cpu baseline:", result["cpu_baseline"])
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

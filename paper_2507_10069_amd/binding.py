@@ -50,6 +50,9 @@ def load() -> ctypes.CDLL:
         raise FileNotFoundError(
             "%s is missing: build the HIP library first (python -m paper_2507_10069_amd.build, or "
             "__graft_entry__.build()).  There is no CPU fallback." % LIB_PATH)
+    # The device memory and the streams handed to the library come from PyTorch, so the library must
+    # bind to the HIP runtime PyTorch has loaded: import torch before dlopen-ing libemm.so.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     bp, vp, i32p = ctypes.POINTER(emm_batch), ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
     lib.emm_kv_scatter.restype = ctypes.c_int
