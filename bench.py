@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--workload", type=int, default=3, help="named workload 1..5 (default 3, the target)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 5 times (a kernel of known HBM traffic, used to "
+                         "scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--others", action="store_true", help="also time the other named workloads (stderr + JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -105,6 +108,14 @@ def main():
         sys.exit("bench.py: no GPU visible")
     B.load()                                            # fails loudly if libemm.so has not been built
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     wl = W.config(args.workload)
     dw = B.DeviceWorkload(wl)
