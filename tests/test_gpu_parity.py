@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 BF16_MAX_ABS, BF16_MEAN_ABS = 2e-2, 2e-3
 F32_MAX_ABS = 1e-4
-LSE_ABS = 2e-3
+LSE_ABS = 4e-3   # l is the sum of the bf16-rounded weights: relative error up to 2^-9 when one key dominates
 
 
 def _gpu_run(wl, poison_unused=False):
