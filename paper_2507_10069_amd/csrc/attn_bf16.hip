@@ -50,7 +50,11 @@ constexpr int BR = 256;           // rows per workgroup
 constexpr int NTHREADS = 512;
 constexpr int BC = 64;            // keys per tile
 constexpr int KV_BYTES = BC * D * 2;   // one K or V tile in LDS: 64 rows of 256 bytes
+constexpr int NBUF = 4;             // depth of the K and of the V tile ring in LDS (tile t lives in slot t % NBUF)
 constexpr int NUM_XCD = 8;
+#ifndef EMM_VALU_PER_MFMA
+#define EMM_VALU_PER_MFMA 6
+#endif
 constexpr float RESCALE_LOG2 = 8.0f;   // slack of the lagging maximum, in powers of two
 
 __device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
@@ -77,10 +81,22 @@ __device__ inline float pair_sum(float x)
 // tell which LDS bytes such a load will write, would otherwise make every later LDS read wait for
 // it; here the tile being filled is never the tile being read, and completion is awaited
 // explicitly (s_waitcnt vmcnt(0)) before the workgroup barrier that publishes the tile.
-__device__ inline void lds_dma16(const void* gptr, uint32_t lds_byte_offset)
+__device__ inline void lds_dma16(const void* base, uint32_t byte_offset, uint32_t lds_byte_offset)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_byte_offset), "v"(gptr) : "memory");
+#ifndef ABL_NOLOAD
+    // address = base (wave-uniform, SGPR pair) + byte_offset (per lane, 32 bits)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_byte_offset), "v"(byte_offset), "s"(base) : "memory");
+#endif
+}
+
+// Identity the optimiser cannot see through.  Inside the main loop, addresses derived from a per-lane
+// base by one XOR or add are recomputed from such a copy every iteration; hoisted out of the loop as
+// invariants they would cost a dozen registers the loop does not have.
+__device__ inline int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
 }
 
 // in-page LDS row of a key: swap bits 2 and 3 of its index within the 16-key page
@@ -90,8 +106,8 @@ template <bool CAUSAL>
 __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a, int n_row_tiles, int n_units,
                                                                      int units_per_xcd)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * KV_BYTES];   // K0 K1 V0 V1
-    constexpr int V_SM = 2 * KV_BYTES;                       // byte offset of the V buffers
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * KV_BYTES];   // K ring, then V ring
+    constexpr int V_SM = NBUF * KV_BYTES;                    // byte offset of the V buffers
 
     const BatchView& b = a.b;
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of units so
@@ -149,13 +165,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     //      that way give scores the mask removes; V rows past the request's tokens are zeroed in LDS by
     //      the wave that fetched them (zero_v_tail), because 0 * NaN would poison the output.
     const int ld_row = lane >> 4, ld_p = lane & 15;          // row within the 4-row group, physical chunk
-    int k_goff[2], v_goff[2];                                // byte offsets inside a (page, head) slab
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int r16 = 8 * (wave & 1) + 4 * j + ld_row;     // LDS row within the page
-        k_goff[j] = swap23(r16) * 256 + ((ld_p ^ r16) << 4);
-        v_goff[j] = r16 * 256 + ((ld_p ^ ((r16 & 3) << 2)) << 4);
-    }
+    // byte offsets inside a (page, head) slab of what this lane fetches first (rows 8(w&1) + ld_row); the
+    // second fetch (4 rows further down) is derived: for K the key moves by 8 and chunk bit 2 flips, for
+    // V the row moves by 4
+    const int r16 = 8 * (wave & 1) + ld_row;
+    const int k_goff0 = swap23(r16) * 256 + ((ld_p ^ r16) << 4);
+    const int v_goff0 = r16 * 256 + ((ld_p ^ ((r16 & 3) << 2)) << 4);
     const unsigned char* __restrict__ kcb = (const unsigned char*)a.k_cache;
     const unsigned char* __restrict__ vcb = (const unsigned char*)a.v_cache;
     const long long slab_bytes = (long long)b.num_kv_heads * 4096;   // one page, all heads
@@ -179,15 +194,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     };
     auto load_k = [&](int kt, int kbuf) {
         const unsigned char* src = kcb + slab_of(kt);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            lds_dma16(src + k_goff[j], smem_base + kbuf * KV_BYTES + ld_lds + j * 1024);
+        const int g0 = opaque(k_goff0);
+        lds_dma16(src, g0, smem_base + kbuf * KV_BYTES + ld_lds);
+        lds_dma16(src, (g0 ^ 64) + 2048, smem_base + kbuf * KV_BYTES + ld_lds + 1024);
     };
     auto load_v = [&](int kt, int vbuf) {
         const unsigned char* src = vcb + slab_of(kt);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            lds_dma16(src + v_goff[j], smem_base + V_SM + vbuf * KV_BYTES + ld_lds + j * 1024);
+        const int g0 = opaque(v_goff0);
+        lds_dma16(src, g0, smem_base + V_SM + vbuf * KV_BYTES + ld_lds);
+        lds_dma16(src, g0 + 1024, smem_base + V_SM + vbuf * KV_BYTES + ld_lds + 1024);
     };
     // after this wave's loads of V tile kt have landed: zero the rows (keys) it fetched that lie past
     // the request's tokens.  Only the request's last tile can have such rows.
@@ -203,20 +218,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     };
 
     // ---- per-wave LDS read addresses (loop invariant per lane; buffer and block offsets are immediates)
-    // K operand: row 32kb + l32, logical chunk 2st + h32 -> physical (2st + h32) ^ (l32 & 15)
-    int k_rd[8];
-#pragma unroll
-    for (int st = 0; st < 8; ++st) k_rd[st] = l32 * 256 + (((2 * st + h32) ^ (l32 & 15)) << 4);
+    // K operand: row 32kb + l32, logical chunk 2st + h32 -> physical (2st + h32) ^ (l32 & 15).  The step
+    // index only touches address bits 5..7, so the address of step st is k_rd0 ^ (st << 5).
+    const int k_rd0 = l32 * 256 + ((h32 ^ (l32 & 15)) << 4);
+    auto k_rd = [&](int st) { return k_rd0 ^ (st << 5); };
+
     // V operand through the transposing read: within each 16-lane group, lane j supplies the address of
     // 4 channels of key k0 + j/4 and receives keys k0 .. k0+3 of channel d0 + j (d0 = first channel of
     // the group), so two reads give the 8 consecutive keys of one channel that the MFMA A operand wants.
-    int v_rd[4];
-    {
-        const int j = lane & 15, g1 = (lane >> 4) & 1;
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-            v_rd[nb] = V_SM + (8 * h32 + (j >> 2)) * 256 + ((4 * (nb ^ (j >> 2)) + 2 * g1 + ((j & 3) >> 1)) << 4) + (j & 1) * 8;
-    }
+    // The channel block nb only touches address bits 6..7: v_rd(nb) = v_rd0 ^ (nb << 6).
+    const int v_rd0 = V_SM + (8 * h32 + ((lane & 15) >> 2)) * 256 +
+                      ((4 * ((lane & 15) >> 2) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) + (lane & 1) * 8;
+    auto v_rd = [&](int nb) { return v_rd0 ^ (nb << 6); };
 
     auto qk_tile = [&](int kbuf, f32x16 (&s)[2]) {          // S^T = K Q^T for the 64 keys of a tile
 #pragma unroll
@@ -227,7 +240,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         for (int st = 0; st < 8; ++st)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {                 // two independent accumulation chains
-                const bf16x8 kf = *(const bf16x8*)(smem + kbuf * KV_BYTES + kb * 32 * 256 + k_rd[st]);
+#ifdef ABL_NOLDSREAD
+                const bf16x8 kf = qf[(st + kb + 1) & 7];
+#else
+                const bf16x8 kf = *(const bf16x8*)(smem + kbuf * KV_BYTES + kb * 32 * 256 + k_rd(st));
+#endif
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
             }
     };
@@ -247,19 +264,25 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 for (int nb = 0; nb < 4; ++nb) {             // four independent accumulation chains
                     typedef short s16x4 __attribute__((ext_vector_type(4)));
                     typedef short s16x8 __attribute__((ext_vector_type(8)));
-                    const unsigned char* src = smem + vbuf * KV_BYTES + (32 * kb + 16 * s) * 256 + v_rd[nb];
+                    const unsigned char* src = smem + vbuf * KV_BYTES + (32 * kb + 16 * s) * 256 + v_rd(nb);
                     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (__attribute__((address_space(3))) s16x4*)(src));
                     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
                     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#ifdef ABL_NOLDSREAD
+                    const bf16x8 vf = qf[(nb + s + kb) & 7];
+#else
                     const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+#endif
                     o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p[kb][s], o_acc[nb], 0, 0, 0);
                 }
     };
 
     float m_run = -INFINITY, l_run = 0.f;
-    const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
+    // log2(e) * scale, wave-uniform: kept in a scalar register
+    const float c_log2 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
+        __builtin_bit_cast(int, b.softmax_scale * 1.44269504088896340736f)));
 
     // P = exp2(S c - m c) rounded to bf16; l accumulates the rounded values (the same numbers the value
     // product uses) with one dot-product instruction per pair
@@ -274,8 +297,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 #pragma unroll
             for (int v = 0; v < 16; v += 2) {
                 bf16x2 pr;
+#ifdef ABL_NOEXP
+                pr[0] = (__bf16)(fmaf(s[kb][v], c_log2, -mc));
+                pr[1] = (__bf16)(fmaf(s[kb][v + 1], c_log2, -mc));
+#else
                 pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v], c_log2, -mc));
                 pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v + 1], c_log2, -mc));
+#endif
 #ifdef EMM_NO_DOT2
                 psum += (float)pr[0] + (float)pr[1];
 #else
@@ -310,11 +338,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     };
 
     if (n_tiles > 0) {
-        // ---- prologue: K(0), V(0), K(1) on their way to LDS
+        // ---- prologue: K(0), V(0), K(1), V(1), K(2) on their way to LDS
         refill_pages(0);
         load_k(0, 0);
         load_v(0, 0);
         load_k(1, 1);
+        load_v(1, 1);
+        load_k(2, 2);
         __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0): this wave's rows have landed
         zero_v_tail(0, 0);
         __syncthreads();
@@ -325,24 +355,135 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         qk_tile(0, sc[0]);
         if (n_clear < 1) mask_tile(0, sc[0]);
         m_run = row_max(sc[0]);                              // finite: key 0 is visible to every row
-        __syncthreads();                                     // K buffer 0 is refilled in iteration 0
 
-        // Iteration i (parity PAR = i & 1 fixed at compile time so that buffer offsets and register roles
-        // are static): S(i+1) and P(i) in the first half, O += V(i)^T P(i), staging and the row maximum
-        // of S(i+1) in the second.  K(i+1) is in K buffer PAR^1, V(i) in V buffer PAR.
+        // Iteration i (R = i % 4 fixed at compile time so that buffer offsets and register roles are
+        // static).  K(i+1) is in K slot (R+1)%4, V(i) in V slot R, S(i) in sc[R & 1].  The tiles fetched
+        // here, K(i+3) and V(i+2), are first read two iterations later.
+        // The body is written as 32 slices, one MFMA each, fenced by scheduling barriers so that the
+        // issue order is the one written here: the matrix pipe gets an instruction every slice and the
+        // softmax arithmetic fills the VALU slots in between.
+        //   slices  0..15  S(i+1) = K(i+1) Q^T        + exp2 work on S(i), key block 0 then 1; tile fetches
+        //   slices 16..23  O += V(i)^T P(i), block 0  + rest of the exp2 work (block 1)
+        //   slices 24..31  O += V(i)^T P(i), block 1  + row maximum of S(i+1)
+        // Operands are read from LDS two slices ahead of their MFMA.
         auto iteration = [&](int i, auto par, auto masked) {
-            constexpr int PAR = decltype(par)::value;
-            load_k(i + 2, PAR);                              // K(i+2) replaces K(i), read last iteration
-            load_v(i + 1, PAR ^ 1);                          // V(i+1) replaces V(i-1)
-            qk_tile(PAR ^ 1, sc[PAR ^ 1]);
-            exp_tile(sc[PAR], pf);
-            __builtin_amdgcn_sched_barrier(0);               // keep the two halves apart (register pressure)
-            pv_tile(PAR, pf);
-            if (decltype(masked)::value) mask_tile(i + 1, sc[PAR ^ 1]);
+            constexpr int R = decltype(par)::value;
+            constexpr bool MASKED = decltype(masked)::value;
+            f32x16 (&s_cur)[2] = sc[R & 1];
+            f32x16 (&s_nxt)[2] = sc[(R & 1) ^ 1];
+            const float mc = m_run * c_log2;
+            bf16x2 ones;
+            ones[0] = (__bf16)1.f;
+            ones[1] = (__bf16)1.f;
+            float psum = 0.f, e0 = 0.f, e1 = 0.f;
+            // softmax work in 48 steps of two VALU instructions: unit u = steps 3u, 3u+1, 3u+2 turns scores
+            // 2u, 2u+1 (block u/8, registers 2(u%8), 2(u%8)+1) into a bf16 pair of P and adds it to l
+            auto softmax_step = [&](int step) {
+                const int u = step / 3, part = step % 3;
+                const int kb = u >> 3, v = 2 * (u & 7);
+#ifdef ABL_NOEXP
+                if (part == 0) e0 = (fmaf(s_cur[kb][v], c_log2, -mc));
+                else if (part == 1) e1 = (fmaf(s_cur[kb][v + 1], c_log2, -mc));
+#elif defined(ABL_NOSOFTMAX)
+                if (part == 0) e0 = s_cur[kb][v];
+                else if (part == 1) e1 = s_cur[kb][v + 1];
+#else
+                if (part == 0) e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v], c_log2, -mc));
+                else if (part == 1) e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v + 1], c_log2, -mc));
+#endif
+                else {
+                    bf16x2 pr;
+                    pr[0] = (__bf16)e0;
+                    pr[1] = (__bf16)e1;
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+                    pf[kb][v >> 3][v & 7] = pr[0];
+                    pf[kb][v >> 3][(v & 7) + 1] = pr[1];
+                }
+            };
+            const int k_base = opaque(k_rd0), v_base = opaque(v_rd0);
+            auto read_k = [&](int k) -> bf16x8 {             // operand of QK slice k: step k/2, key block k%2
+#ifdef ABL_NOLDSREAD
+                return qf[(k + 1) & 7];
+#else
+                return *(const bf16x8*)(smem + ((R + 1) & 3) * KV_BYTES + (k & 1) * 32 * 256 + (k_base ^ ((k >> 1) << 5)));
+#endif
+            };
+            auto read_v = [&](int k) -> bf16x8 {             // operand of PV slice k: kb = k/8, s = (k/4)%2, nb = k%4
+                typedef short s16x4 __attribute__((ext_vector_type(4)));
+                typedef short s16x8 __attribute__((ext_vector_type(8)));
+                const unsigned char* src = smem + R * KV_BYTES + (32 * (k >> 3) + 16 * ((k >> 2) & 1)) * 256 + (v_base ^ ((k & 3) << 6));
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
+#ifdef ABL_NOLDSREAD
+                return qf[(k + 3) & 7];
+#else
+                return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#endif
+            };
+
+            bf16x8 opnd[34];                                 // operands in flight (short live ranges)
+            opnd[0] = read_k(0);
+            opnd[1] = read_k(1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                opnd[k + 2] = (k + 2 < 16) ? read_k(k + 2) : read_v(k + 2 - 16);
+                if (k < 2) {
+                    f32x16 zero;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                    s_nxt[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[k], qf[k >> 1], zero, 0, 0, 0);
+                } else {
+                    s_nxt[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[k], qf[k >> 1], s_nxt[k & 1], 0, 0, 0);
+                }
+                softmax_step(2 * k);
+                softmax_step(2 * k + 1);
+                // fetch the tiles that are first read two iterations from now (slots last read two
+                // iterations ago), once the matrix pipe has work queued
+                if (k == 2) load_k(i + 3, (R + 3) & 3);
+                if (k == 4) load_v(i + 2, (R + 2) & 3);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // Mid-iteration publish point.  K(i+2) and V(i+1), fetched one iteration ago, must have landed
+            // (the four loads issued above may stay in flight); the barrier makes them visible to all
+            // waves well before iteration i+1 needs them, and sits where every wave still has MFMAs in
+            // flight and its next operands already on the way.
+            __builtin_amdgcn_s_waitcnt(0x0f74);              // vmcnt(4)
+            // a tile with keys past the request's tokens lies beyond every wave's n_clear, so only the
+            // masked variant can meet one
+            if (MASKED) zero_v_tail(i + 1, (R + 1) & 3);
+#ifndef ABL_NOBARRIER
+            __syncthreads();
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+            float mx = 0.f;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (k + 2 < 16) opnd[16 + k + 2] = read_v(k + 2);
+                o_acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[16 + k], pf[k >> 3][(k >> 2) & 1],
+                                                                       o_acc[k & 3], 0, 0, 0);
+                if (k < 8) {
+                    softmax_step(32 + 2 * k);
+                    softmax_step(32 + 2 * k + 1);
+                } else if (!MASKED) {
+                    // row maximum of S(i+1): 32 values, four per slice
+                    const int kb = (k - 8) >> 2, v = 4 * ((k - 8) & 3);
+                    const float m4 = fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]));
+                    mx = (k == 8) ? m4 : fmaxf(mx, m4);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            l_run += psum;
+            if (MASKED) {
+                mask_tile(i + 1, s_nxt);
+                mx = row_max(s_nxt);
+            } else {
+                mx = pair_max(mx);
+            }
             // The running maximum only has to keep exp2 in range, so it is raised (and O, l rescaled)
             // only when a row's new maximum exceeds it by more than 2^RESCALE_LOG2.  Both lanes of a row
             // hold the same m_run and the same maximum, so they decide alike.
-            const float m_cand = fmaxf(m_run, row_max(sc[PAR ^ 1]));
+            const float m_cand = fmaxf(m_run, mx);
             const bool raise = (m_cand - m_run) * c_log2 > RESCALE_LOG2;
             if (__builtin_amdgcn_ballot_w64(raise) != 0) {
                 const float m_new = raise ? m_cand : m_run;
@@ -354,48 +495,67 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o_acc[nb][v] *= alpha;
             }
-            __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0): K(i+2), V(i+1) rows of this wave landed
-            zero_v_tail(i + 1, PAR ^ 1);
-            __syncthreads();
         };
         // iteration i takes the maximum of tile i+1: unmasked while i+1 < n_clear.  Every wave runs
         // n_tiles-1 iterations in total (one barrier each), split differently between the two loops.
         const int n_plain = max(0, min(n_clear - 1, n_tiles - 1));
         int i = 0;
-        // hot loop: two tiles per trip, straight-line (tile parity is the position in the body)
-        for (; i + 2 <= n_plain; i += 2) {
-            if (i + 3 - pg_base >= 64) refill_pages(i + 1);  // tiles i+1 .. i+3 are fetched in this trip
+        // hot loop: four tiles per trip, straight-line (a tile's ring slot is its position in the body)
+        for (; i + 4 <= n_plain; i += 4) {
+            if (i + 6 - pg_base >= 64) refill_pages(i + 2);  // tiles i+2 .. i+6 are fetched in this trip
             iteration(i, std::integral_constant<int, 0>{}, std::false_type{});
             iteration(i + 1, std::integral_constant<int, 1>{}, std::false_type{});
+            iteration(i + 2, std::integral_constant<int, 2>{}, std::false_type{});
+            iteration(i + 3, std::integral_constant<int, 3>{}, std::false_type{});
         }
-        // remaining tiles (the ones that touch the diagonal or the end of the key range)
+        // remaining tiles (at most three unmasked ones, then those that touch the diagonal or the end
+        // of the key range); masking a tile that does not need it is harmless
         for (; i + 1 < n_tiles; ++i) {
-            if (i + 2 - pg_base >= 64) refill_pages(i + 1);
-            if (i & 1) iteration(i, std::integral_constant<int, 1>{}, std::true_type{});
-            else       iteration(i, std::integral_constant<int, 0>{}, std::true_type{});
+            if (i + 3 - pg_base >= 64) refill_pages(i + 2);
+            switch (i & 3) {
+                case 0: iteration(i, std::integral_constant<int, 0>{}, std::true_type{}); break;
+                case 1: iteration(i, std::integral_constant<int, 1>{}, std::true_type{}); break;
+                case 2: iteration(i, std::integral_constant<int, 2>{}, std::true_type{}); break;
+                default: iteration(i, std::integral_constant<int, 3>{}, std::true_type{}); break;
+            }
         }
         // ---- tail: tile n-1
-        if ((n_tiles - 1) & 1) { exp_tile(sc[1], pf); pv_tile(1, pf); }
-        else                   { exp_tile(sc[0], pf); pv_tile(0, pf); }
+        switch ((n_tiles - 1) & 3) {
+            case 0: exp_tile(sc[0], pf); pv_tile(0, pf); break;
+            case 1: exp_tile(sc[1], pf); pv_tile(1, pf); break;
+            case 2: exp_tile(sc[0], pf); pv_tile(2, pf); break;
+            default: exp_tile(sc[1], pf); pv_tile(3, pf); break;
+        }
     }
 
-    if (my_row >= n_rows) return;
-    const float l_tot = pair_sum(l_run);                     // partner lane is in the same state
-    const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
-    __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
+    // ---- epilogue.  The row bookkeeping is recomputed from an opaque copy of the thread index so that
+    //      none of it has to stay in registers across the main loop.
+    {
+        int t2 = threadIdx.x;
+        asm volatile("" : "+v"(t2));
+        const int e_l32 = t2 & 31, e_h32 = (t2 >> 5) & 1;
+        const int e_row = row0 + (t2 >> 6) * 32 + e_l32;
+        if (e_row >= n_rows) return;
+        const int e_tok = e_row / G;
+        const int e_hq = kvh * G + (e_row - e_tok * G);
+        const long long e_qrow = (long long)b.cu_new_lens[r] + e_tok;
+        const float l_tot = pair_sum(l_run);                 // partner lane is in the same state
+        const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
+        __bf16* __restrict__ op = (__bf16*)a.out + (e_qrow * b.num_q_heads + e_hq) * D;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            // registers 4*v4 .. 4*v4+3 are channels 32nb + 8*v4 + 4*h32 + 0..3
-            bf16x4 w;
+            for (int v4 = 0; v4 < 4; ++v4) {
+                // registers 4*v4 .. 4*v4+3 are channels 32nb + 8*v4 + 4*h32 + 0..3
+                bf16x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[nb][4 * v4 + e] * inv);
-            *(bf16x4*)(op + 32 * nb + 8 * v4 + 4 * h32) = w;
-        }
-    if (a.lse != nullptr && h32 == 0)
-        a.lse[q_row * b.num_q_heads + hq] =
-            (l_tot > 0.f) ? m_run * b.softmax_scale + logf(l_tot) : -INFINITY;
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[nb][4 * v4 + e] * inv);
+                *(bf16x4*)(op + 32 * nb + 8 * v4 + 4 * e_h32) = w;
+            }
+        if (a.lse != nullptr && e_h32 == 0)
+            a.lse[e_qrow * b.num_q_heads + e_hq] =
+                (l_tot > 0.f) ? m_run * b.softmax_scale + logf(l_tot) : -INFINITY;
+    }
 }
 
 }  // namespace
