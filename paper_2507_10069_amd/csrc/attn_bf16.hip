@@ -103,22 +103,24 @@ __device__ inline int opaque(int x)
 __device__ inline int swap23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
 template <bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a, int n_row_tiles, int n_units,
-                                                                     int units_per_xcd)
+__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a, int n_row_tiles, int n_pairs)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * KV_BYTES];   // K ring, then V ring
     constexpr int V_SM = NBUF * KV_BYTES;                    // byte offset of the V buffers
 
     const BatchView& b = a.b;
-    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of units so
-    // that the row tiles that stream the same (request, KV head) pages share that XCD's L2.
-    const int unit = (blockIdx.x % NUM_XCD) * units_per_xcd + blockIdx.x / NUM_XCD;
-    if (unit >= n_units) return;
+    // Workgroups are dealt to the 8 XCDs round-robin.  The (request, KV head) pairs are dealt to the XCDs
+    // round-robin as well -- the KV heads of one request cost the same, so this balances the XCDs whatever
+    // the request lengths are -- and an XCD works through its pairs one after the other, row tiles from
+    // the last (longest key range) to the first, so that the workgroups running together on an XCD mostly
+    // stream the same pages through its L2.
     const int G = b.num_q_heads / b.num_kv_heads;
-    int rest = unit;
-    const int tile = n_row_tiles - 1 - rest % n_row_tiles;   rest /= n_row_tiles;   // long tiles first
-    const int kvh = rest % b.num_kv_heads;
-    const int r = rest / b.num_kv_heads;
+    const int xcd = blockIdx.x % NUM_XCD, in_xcd = blockIdx.x / NUM_XCD;
+    const int pair = xcd + NUM_XCD * (in_xcd / n_row_tiles);
+    if (pair >= n_pairs) return;
+    const int tile = n_row_tiles - 1 - in_xcd % n_row_tiles;
+    const int kvh = pair % b.num_kv_heads;
+    const int r = pair / b.num_kv_heads;
 
     const int N = b.new_lens[r];
     const int n_rows = N * G;                                // rows of this (request, KV head)
@@ -366,9 +368,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         //   slices 16..23  O += V(i)^T P(i), block 0  + rest of the exp2 work (block 1)
         //   slices 24..31  O += V(i)^T P(i), block 1  + row maximum of S(i+1)
         // Operands are read from LDS two slices ahead of their MFMA.
-        auto iteration = [&](int i, auto par, auto masked) {
+        auto iteration = [&](int i, auto par) {
             constexpr int R = decltype(par)::value;
-            constexpr bool MASKED = decltype(masked)::value;
+            // tile i+1 needs masking / may hold keys past the request's tokens (both wave-uniform, both rare)
+            const bool needs_mask = i + 1 >= n_clear;
             f32x16 (&s_cur)[2] = sc[R & 1];
             f32x16 (&s_nxt)[2] = sc[(R & 1) ^ 1];
             const float mc = m_run * c_log2;
@@ -449,9 +452,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             // waves well before iteration i+1 needs them, and sits where every wave still has MFMAs in
             // flight and its next operands already on the way.
             __builtin_amdgcn_s_waitcnt(0x0f74);              // vmcnt(4)
-            // a tile with keys past the request's tokens lies beyond every wave's n_clear, so only the
-            // masked variant can meet one
-            if (MASKED) zero_v_tail(i + 1, (R + 1) & 3);
+            if (needs_mask) zero_v_tail(i + 1, (R + 1) & 3);  // such a tile lies beyond every wave's n_clear
 #ifndef ABL_NOBARRIER
             __syncthreads();
 #endif
@@ -462,10 +463,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 if (k + 2 < 16) opnd[16 + k + 2] = read_v(k + 2);
                 o_acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[16 + k], pf[k >> 3][(k >> 2) & 1],
                                                                        o_acc[k & 3], 0, 0, 0);
+                if (k == 8 && needs_mask) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    mask_tile(i + 1, s_nxt);                 // before the maximum of S(i+1) is taken
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 if (k < 8) {
                     softmax_step(32 + 2 * k);
                     softmax_step(32 + 2 * k + 1);
-                } else if (!MASKED) {
+                } else {
                     // row maximum of S(i+1): 32 values, four per slice
                     const int kb = (k - 8) >> 2, v = 4 * ((k - 8) & 3);
                     const float m4 = fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]));
@@ -474,12 +480,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 __builtin_amdgcn_sched_barrier(0);
             }
             l_run += psum;
-            if (MASKED) {
-                mask_tile(i + 1, s_nxt);
-                mx = row_max(s_nxt);
-            } else {
-                mx = pair_max(mx);
-            }
+            mx = pair_max(mx);
             // The running maximum only has to keep exp2 in range, so it is raised (and O, l rescaled)
             // only when a row's new maximum exceeds it by more than 2^RESCALE_LOG2.  Both lanes of a row
             // hold the same m_run and the same maximum, so they decide alike.
@@ -496,29 +497,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                     for (int v = 0; v < 16; ++v) o_acc[nb][v] *= alpha;
             }
         };
-        // iteration i takes the maximum of tile i+1: unmasked while i+1 < n_clear.  Every wave runs
-        // n_tiles-1 iterations in total (one barrier each), split differently between the two loops.
-        const int n_plain = max(0, min(n_clear - 1, n_tiles - 1));
+        // four tiles per trip, straight-line (a tile's ring slot is its position in the body), then up to
+        // three more; every wave runs n_tiles-1 iterations, one barrier each
         int i = 0;
-        // hot loop: four tiles per trip, straight-line (a tile's ring slot is its position in the body)
-        for (; i + 4 <= n_plain; i += 4) {
+        for (; i + 4 < n_tiles; i += 4) {
             if (i + 6 - pg_base >= 64) refill_pages(i + 2);  // tiles i+2 .. i+6 are fetched in this trip
-            iteration(i, std::integral_constant<int, 0>{}, std::false_type{});
-            iteration(i + 1, std::integral_constant<int, 1>{}, std::false_type{});
-            iteration(i + 2, std::integral_constant<int, 2>{}, std::false_type{});
-            iteration(i + 3, std::integral_constant<int, 3>{}, std::false_type{});
+            iteration(i, std::integral_constant<int, 0>{});
+            iteration(i + 1, std::integral_constant<int, 1>{});
+            iteration(i + 2, std::integral_constant<int, 2>{});
+            iteration(i + 3, std::integral_constant<int, 3>{});
         }
-        // remaining tiles (at most three unmasked ones, then those that touch the diagonal or the end
-        // of the key range); masking a tile that does not need it is harmless
-        for (; i + 1 < n_tiles; ++i) {
-            if (i + 3 - pg_base >= 64) refill_pages(i + 2);
-            switch (i & 3) {
-                case 0: iteration(i, std::integral_constant<int, 0>{}, std::true_type{}); break;
-                case 1: iteration(i, std::integral_constant<int, 1>{}, std::true_type{}); break;
-                case 2: iteration(i, std::integral_constant<int, 2>{}, std::true_type{}); break;
-                default: iteration(i, std::integral_constant<int, 3>{}, std::true_type{}); break;
-            }
-        }
+        if (i + 5 - pg_base >= 64) refill_pages(i + 2);      // the leftover iterations fetch tiles i+2 .. i+5
+        if (i + 1 < n_tiles) iteration(i, std::integral_constant<int, 0>{});
+        if (i + 2 < n_tiles) iteration(i + 1, std::integral_constant<int, 1>{});
+        if (i + 3 < n_tiles) iteration(i + 2, std::integral_constant<int, 2>{});
         // ---- tail: tile n-1
         switch ((n_tiles - 1) & 3) {
             case 0: exp_tile(sc[0], pf); pv_tile(0, pf); break;
@@ -567,16 +559,16 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     const int G = b.num_q_heads / b.num_kv_heads;
     const long long max_rows = (long long)b.max_new_len * G;
     const long long n_row_tiles = (max_rows + BR - 1) / BR;
-    const long long n_units = n_row_tiles * b.num_reqs * b.num_kv_heads;
-    if (n_units > 0x3fffffff) return hipErrorInvalidValue;
-    const int units_per_xcd = (int)((n_units + NUM_XCD - 1) / NUM_XCD);
-    const unsigned grid = (unsigned)units_per_xcd * NUM_XCD;
+    const long long n_pairs = (long long)b.num_reqs * b.num_kv_heads;
+    const long long pairs_per_xcd = (n_pairs + NUM_XCD - 1) / NUM_XCD;
+    const long long grid = NUM_XCD * pairs_per_xcd * n_row_tiles;
+    if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)
-        hipLaunchKernelGGL(attn_bf16_d128_kernel<true>, dim3(grid), dim3(NTHREADS), 0, stream, a,
-                           (int)n_row_tiles, (int)n_units, units_per_xcd);
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<true>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a,
+                           (int)n_row_tiles, (int)n_pairs);
     else
-        hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3(grid), dim3(NTHREADS), 0, stream, a,
-                           (int)n_row_tiles, (int)n_units, units_per_xcd);
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a,
+                           (int)n_row_tiles, (int)n_pairs);
     return hipGetLastError();
 }
 
