@@ -55,6 +55,10 @@ constexpr int NUM_XCD = 8;
 #ifndef EMM_VALU_PER_MFMA
 #define EMM_VALU_PER_MFMA 6
 #endif
+#ifndef EMM_PF_DIST
+#define EMM_PF_DIST 2
+#endif
+constexpr int PF_DIST = EMM_PF_DIST;   // MFMA operands are read from LDS this many slices ahead
 constexpr float RESCALE_LOG2 = 8.0f;   // slack of the lagging maximum, in powers of two
 
 __device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
@@ -367,7 +371,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         //   slices  0..15  S(i+1) = K(i+1) Q^T        + exp2 work on S(i), key block 0 then 1; tile fetches
         //   slices 16..23  O += V(i)^T P(i), block 0  + rest of the exp2 work (block 1)
         //   slices 24..31  O += V(i)^T P(i), block 1  + row maximum of S(i+1)
-        // Operands are read from LDS two slices ahead of their MFMA.
+        // Operands are read from LDS PF_DIST slices ahead of their MFMA.
         auto iteration = [&](int i, auto par) {
             constexpr int R = decltype(par)::value;
             // tile i+1 needs masking / may hold keys past the request's tokens (both wave-uniform, both rare)
@@ -424,13 +428,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 #endif
             };
 
-            bf16x8 opnd[34];                                 // operands in flight (short live ranges)
-            opnd[0] = read_k(0);
-            opnd[1] = read_k(1);
+            bf16x8 opnd[32 + PF_DIST];                       // operands in flight (short live ranges)
+#pragma unroll
+            for (int k = 0; k < PF_DIST; ++k) opnd[k] = read_k(k);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                opnd[k + 2] = (k + 2 < 16) ? read_k(k + 2) : read_v(k + 2 - 16);
+                opnd[k + PF_DIST] = (k + PF_DIST < 16) ? read_k(k + PF_DIST) : read_v(k + PF_DIST - 16);
                 if (k < 2) {
                     f32x16 zero;
 #pragma unroll
@@ -460,7 +464,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             float mx = 0.f;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                if (k + 2 < 16) opnd[16 + k + 2] = read_v(k + 2);
+                if (k + PF_DIST < 16) opnd[16 + k + PF_DIST] = read_v(k + PF_DIST);
                 o_acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[16 + k], pf[k >> 3][(k >> 2) & 1],
                                                                        o_acc[k & 3], 0, 0, 0);
                 if (k == 8 && needs_mask) {
