@@ -11,9 +11,9 @@
 //   workgroup = 8 waves = 256 consecutive rows of one (request, KV head); 2 waves per SIMD;
 //   wave      = 32 rows, all 128 channels;
 //   KV loop   = tiles of 64 keys (4 pages), in logical order.
-// Per tile the 4 pages of K and of V for the KV head are read from L2/HBM as whole 4 KB slabs
-// (coalesced), register-staged one iteration ahead and written to LDS (K row-major with padded
-// rows, V transposed in registers and XOR-swizzled); v_mfma_f32_32x32x16_bf16 consumes them.
+// Per tile the 4 pages of K and of V for the KV head go straight from L2/HBM into LDS (LDS-DMA loads,
+// 16 bytes per lane, whole 4 KB page slabs), row-major with XOR-swizzled 16-byte chunks; K is consumed
+// with ds_read_b128, V with the transposing ds_read_b64_tr_b16, both by v_mfma_f32_32x32x16_bf16.
 //
 // Orientation.  Scores are produced transposed, S^T = K Q^T, so that an accumulator lane owns ONE
 // query row (column l%32 of the 32x32 result) and 16 of the 32 keys of a block; the other 16 sit
@@ -24,14 +24,15 @@
 // lane are exactly the 8 consecutive keys the B operand of the value product expects from it, so
 // P goes from the score accumulators to the PV operand without leaving registers.
 //
-// Software pipeline.  A single wave issues a plain VALU instruction only about every 8 cycles and
-// an MFMA occupies the matrix pipe for 32, so the softmax arithmetic is placed inside the MFMA
-// stream of the same wave: iteration i computes S(i+1) = K(i+1) Q^T (16 MFMA) while the VALU turns
-// S(i) into P(i) = exp2(S(i) - m), then O += V(i)^T P(i) (16 MFMA) while the VALU stages the next
-// tiles into LDS and takes the row maximum of S(i+1).  The running maximum m may lag the true
-// maximum by up to 2^8 (it only has to keep exp2 in range); O and l are rescaled only when a row
-// exceeds that.  K and V tiles are double buffered in LDS with one workgroup barrier per tile; the
-// loop body exists in two copies (tile parity) so buffer offsets and register roles are static.
+// Software pipeline.  The softmax arithmetic is placed inside the MFMA stream of the same wave:
+// the iteration for tile i computes S(i+1) = K(i+1) Q^T (16 MFMA) while the VALU turns S(i) into
+// P(i) = exp2(S(i) - m), then O += V(i)^T P(i) (16 MFMA) while the VALU takes the row maximum of
+// S(i+1); the body is written as 32 one-MFMA slices fenced by scheduling barriers, so the issue
+// order is the written one.  The running maximum m may lag the true maximum by up to 2^8 (it only
+// has to keep exp2 in range); O and l are rescaled only when a row exceeds that.  K and V tiles
+// live in 4-deep rings in LDS, fetched two iterations ahead, with one workgroup barrier per tile
+// placed mid-iteration; the loop body exists in four copies (ring slot) so buffer offsets and
+// register roles are compile-time constants.
 #include "emm_internal.h"
 
 #include <type_traits>
@@ -52,17 +53,8 @@ constexpr int BC = 64;            // keys per tile
 constexpr int KV_BYTES = BC * D * 2;   // one K or V tile in LDS: 64 rows of 256 bytes
 constexpr int NBUF = 4;             // depth of the K and of the V tile ring in LDS (tile t lives in slot t % NBUF)
 constexpr int NUM_XCD = 8;
-#ifndef EMM_VALU_PER_MFMA
-#define EMM_VALU_PER_MFMA 6
-#endif
-#ifndef EMM_PF_DIST
-#define EMM_PF_DIST 2
-#endif
-constexpr int PF_DIST = EMM_PF_DIST;   // MFMA operands are read from LDS this many slices ahead
+constexpr int PF_DIST = 2;          // MFMA operands are read from LDS this many slices ahead of their use
 constexpr float RESCALE_LOG2 = 8.0f;   // slack of the lagging maximum, in powers of two
-
-__device__ inline uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ inline uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
 // A query row lives in lanes l and l^32 (16 of a block's 32 keys each).  v_permlane32_swap with the
 // same register as both operands leaves the low half's value in every lane of the first result and
@@ -87,11 +79,9 @@ __device__ inline float pair_sum(float x)
 // explicitly (s_waitcnt vmcnt(0)) before the workgroup barrier that publishes the tile.
 __device__ inline void lds_dma16(const void* base, uint32_t byte_offset, uint32_t lds_byte_offset)
 {
-#ifndef ABL_NOLOAD
     // address = base (wave-uniform, SGPR pair) + byte_offset (per lane, 32 bits)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_byte_offset), "v"(byte_offset), "s"(base) : "memory");
-#endif
 }
 
 // Identity the optimiser cannot see through.  Inside the main loop, addresses derived from a per-lane
@@ -246,11 +236,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         for (int st = 0; st < 8; ++st)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {                 // two independent accumulation chains
-#ifdef ABL_NOLDSREAD
-                const bf16x8 kf = qf[(st + kb + 1) & 7];
-#else
                 const bf16x8 kf = *(const bf16x8*)(smem + kbuf * KV_BYTES + kb * 32 * 256 + k_rd(st));
-#endif
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
             }
     };
@@ -276,11 +262,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                         (__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
                     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#ifdef ABL_NOLDSREAD
-                    const bf16x8 vf = qf[(nb + s + kb) & 7];
-#else
                     const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-#endif
                     o_acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p[kb][s], o_acc[nb], 0, 0, 0);
                 }
     };
@@ -303,18 +285,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 #pragma unroll
             for (int v = 0; v < 16; v += 2) {
                 bf16x2 pr;
-#ifdef ABL_NOEXP
-                pr[0] = (__bf16)(fmaf(s[kb][v], c_log2, -mc));
-                pr[1] = (__bf16)(fmaf(s[kb][v + 1], c_log2, -mc));
-#else
                 pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v], c_log2, -mc));
                 pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v + 1], c_log2, -mc));
-#endif
-#ifdef EMM_NO_DOT2
-                psum += (float)pr[0] + (float)pr[1];
-#else
                 psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
-#endif
                 p[kb][v >> 3][v & 7] = pr[0];
                 p[kb][v >> 3][(v & 7) + 1] = pr[1];
             }
@@ -388,16 +361,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             auto softmax_step = [&](int step) {
                 const int u = step / 3, part = step % 3;
                 const int kb = u >> 3, v = 2 * (u & 7);
-#ifdef ABL_NOEXP
-                if (part == 0) e0 = (fmaf(s_cur[kb][v], c_log2, -mc));
-                else if (part == 1) e1 = (fmaf(s_cur[kb][v + 1], c_log2, -mc));
-#elif defined(ABL_NOSOFTMAX)
-                if (part == 0) e0 = s_cur[kb][v];
-                else if (part == 1) e1 = s_cur[kb][v + 1];
-#else
                 if (part == 0) e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v], c_log2, -mc));
                 else if (part == 1) e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v + 1], c_log2, -mc));
-#endif
                 else {
                     bf16x2 pr;
                     pr[0] = (__bf16)e0;
@@ -409,11 +374,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             };
             const int k_base = opaque(k_rd0), v_base = opaque(v_rd0);
             auto read_k = [&](int k) -> bf16x8 {             // operand of QK slice k: step k/2, key block k%2
-#ifdef ABL_NOLDSREAD
-                return qf[(k + 1) & 7];
-#else
                 return *(const bf16x8*)(smem + ((R + 1) & 3) * KV_BYTES + (k & 1) * 32 * 256 + (k_base ^ ((k >> 1) << 5)));
-#endif
             };
             auto read_v = [&](int k) -> bf16x8 {             // operand of PV slice k: kb = k/8, s = (k/4)%2, nb = k%4
                 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -421,11 +382,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 const unsigned char* src = smem + R * KV_BYTES + (32 * (k >> 3) + 16 * ((k >> 2) & 1)) * 256 + (v_base ^ ((k & 3) << 6));
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
-#ifdef ABL_NOLDSREAD
-                return qf[(k + 3) & 7];
-#else
                 return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#endif
             };
 
             bf16x8 opnd[32 + PF_DIST];                       // operands in flight (short live ranges)
@@ -457,9 +414,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             // flight and its next operands already on the way.
             __builtin_amdgcn_s_waitcnt(0x0f74);              // vmcnt(4)
             if (needs_mask) zero_v_tail(i + 1, (R + 1) & 3);  // such a tile lies beyond every wave's n_clear
-#ifndef ABL_NOBARRIER
             __syncthreads();
-#endif
             __builtin_amdgcn_sched_barrier(0);
             float mx = 0.f;
 #pragma unroll
