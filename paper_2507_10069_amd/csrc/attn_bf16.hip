@@ -28,7 +28,9 @@
 // the iteration for tile i computes S(i+1) = K(i+1) Q^T (16 MFMA) while the VALU turns S(i) into
 // P(i) = exp2(S(i) - m), then O += V(i)^T P(i) (16 MFMA) while the VALU takes the row maximum of
 // S(i+1); the body is written as 32 one-MFMA slices fenced by scheduling barriers, so the issue
-// order is the written one.  The running maximum m may lag the true maximum by up to 2^8 (it only
+// order is the written one.  The row sums of P (of the bf16-rounded values, so that the normaliser
+// matches the numerator) are taken on the matrix pipe as well, with eight small 4x4x4 MFMAs per tile:
+// dot-product instructions on the VALU do not overlap with MFMAs.  The running maximum m may lag the true maximum by up to 2^8 (it only
 // has to keep exp2 in range); O and l are rescaled only when a row exceeds that.  K and V tiles
 // live in 4-deep rings in LDS, fetched two iterations ahead, with one workgroup barrier per tile
 // placed mid-iteration; the loop body exists in four copies (ring slot) so buffer offsets and
@@ -70,6 +72,23 @@ __device__ inline float pair_sum(float x)
     const uint32_t u = __float_as_uint(x);
     const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Row sums of P on the matrix pipe.  v_mfma_f32_4x4x4_16b_bf16 multiplies, in each group of four lanes, a
+// 4x4 A (lane = row) by a 4x4 B (lane = column, four k values per lane) and adds C (lane = column, four
+// rows per lane).  With A all ones every row of the result is the column sum of B, i.e. each lane gets
+// the sum of the four bf16 values it passed in, in all four result registers.  Eight cycles of the
+// matrix pipe per instruction and no VALU slot; the dot-product instructions that would do the same on
+// the VALU cannot overlap with MFMAs at all.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4v __attribute__((ext_vector_type(4)));
+__device__ inline f32x4 sum4_bf16(const bf16x8& p, int half, f32x4 acc)   // elements 4 half .. 4 half + 3 of p
+{
+    const s16x4v ones = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
+    bf16x4 q;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) q[e] = p[4 * half + e];
+    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones, __builtin_bit_cast(s16x4v, q), acc, 0, 0, 0);
 }
 
 // Asynchronous copy of 16 bytes per lane from global memory straight into LDS: lane i of the wave
@@ -276,22 +295,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // product uses) with one dot-product instruction per pair
     auto exp_tile = [&](const f32x16 (&s)[2], bf16x8 (&p)[2][2]) {
         const float mc = m_run * c_log2;
-        bf16x2 ones;
-        ones[0] = (__bf16)1.f;
-        ones[1] = (__bf16)1.f;
-        float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; v += 2) {
-                bf16x2 pr;
-                pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v], c_log2, -mc));
-                pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v + 1], c_log2, -mc));
-                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
-                p[kb][v >> 3][v & 7] = pr[0];
-                p[kb][v >> 3][(v & 7) + 1] = pr[1];
+                p[kb][v >> 3][v & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v], c_log2, -mc));
+                p[kb][v >> 3][(v & 7) + 1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][v + 1], c_log2, -mc));
             }
-        l_run += psum;
+        f32x4 psum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            psum = sum4_bf16(p[u >> 2][(u >> 1) & 1], u & 1, psum);
+        l_run += psum[0];
     };
 
     // scores of keys a row must not see become -inf (register v of block kb holds key
@@ -352,10 +367,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             f32x16 (&s_cur)[2] = sc[R & 1];
             f32x16 (&s_nxt)[2] = sc[(R & 1) ^ 1];
             const float mc = m_run * c_log2;
-            bf16x2 ones;
-            ones[0] = (__bf16)1.f;
-            ones[1] = (__bf16)1.f;
-            float psum = 0.f, e0 = 0.f, e1 = 0.f;
+            float e0 = 0.f, e1 = 0.f;
+            f32x4 psum = {0.f, 0.f, 0.f, 0.f};
             // softmax work in 48 steps of two VALU instructions: unit u = steps 3u, 3u+1, 3u+2 turns scores
             // 2u, 2u+1 (block u/8, registers 2(u%8), 2(u%8)+1) into a bf16 pair of P and adds it to l
             auto softmax_step = [&](int step) {
@@ -367,7 +380,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                     bf16x2 pr;
                     pr[0] = (__bf16)e0;
                     pr[1] = (__bf16)e1;
-                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
                     pf[kb][v >> 3][v & 7] = pr[0];
                     pf[kb][v >> 3][(v & 7) + 1] = pr[1];
                 }
@@ -378,7 +390,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             };
             auto read_v = [&](int k) -> bf16x8 {             // operand of PV slice k: kb = k/8, s = (k/4)%2, nb = k%4
                 typedef short s16x4 __attribute__((ext_vector_type(4)));
-                typedef short s16x8 __attribute__((ext_vector_type(8)));
                 const unsigned char* src = smem + R * KV_BYTES + (32 * (k >> 3) + 16 * ((k >> 2) & 1)) * 256 + (v_base ^ ((k & 3) << 6));
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
@@ -433,12 +444,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 } else {
                     // row maximum of S(i+1): 32 values, four per slice
                     const int kb = (k - 8) >> 2, v = 4 * ((k - 8) & 3);
-                    const float m4 = fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]));
-                    mx = (k == 8) ? m4 : fmaxf(mx, m4);
+                    // written as max(max(a, b), running) so that each pair costs one three-input maximum
+                    const float m2 = (k == 8) ? fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1])
+                                              : fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), mx);
+                    mx = fmaxf(fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]), m2);
+                }
+                if (k >= 8) {
+                    // row sum of P(i), four values per slice, on the matrix pipe
+                    const int u = k - 8;
+                    psum = sum4_bf16(pf[u >> 2][(u >> 1) & 1], u & 1, psum);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            l_run += psum;
+            l_run += psum[0];
             mx = pair_max(mx);
             // The running maximum only has to keep exp2 in range, so it is raised (and O, l rescaled)
             // only when a row's new maximum exceeds it by more than 2^RESCALE_LOG2.  Both lanes of a row

@@ -116,6 +116,13 @@ int main()
         run<512, 2, 5, 1>("2 waves/SIMD: MFMA + 1 LDS read + 5 VALU + barrier / 32 MFMA", d, out);
         run<256, 1, 5, 0>("1 wave/SIMD:  MFMA + 0.5 LDS read + 5 VALU", d, out);
         run<256, 2, 5, 0>("1 wave/SIMD:  MFMA + 1 LDS read + 5 VALU", d, out);
+        run<512, 2, 4, 0>("2 waves/SIMD: MFMA + 1 LDS read + 4 VALU", d, out);
+        run<512, 2, 3, 0>("2 waves/SIMD: MFMA + 1 LDS read + 3 VALU", d, out);
+        run<256, 1, 4, 0>("1 wave/SIMD:  MFMA + 0.5 LDS read + 4 VALU", d, out);
+        run<256, 1, 3, 0>("1 wave/SIMD:  MFMA + 0.5 LDS read + 3 VALU", d, out);
+        run<256, 1, 0, 0>("1 wave/SIMD:  MFMA + 0.5 LDS read", d, out);
+        run<256, 0, 0, 0>("1 wave/SIMD:  MFMA only", d, out);
+        run<256, 0, 4, 0>("1 wave/SIMD:  MFMA + 4 VALU", d, out);
     }
     return 0;
 }
