@@ -112,6 +112,17 @@ __device__ inline int opaque(int x)
     return x;
 }
 
+// Ties a value to the place in the instruction stream where it is written: without it the optimiser
+// gathers the softmax arithmetic of several slices into one clump behind the next branch, and the
+// matrix pipe idles while both waves of a SIMD work through it.  Emits no instruction.
+__device__ inline void pin(float& x) { asm volatile("" : "+v"(x)); }
+__device__ inline void pin(bf16x2& x)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    asm volatile("" : "+v"(u));
+    x = __builtin_bit_cast(bf16x2, u);
+}
+
 // in-page LDS row of a key: swap bits 2 and 3 of its index within the 16-key page
 __device__ inline int swap23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
@@ -374,12 +385,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             auto softmax_step = [&](int step) {
                 const int u = step / 3, part = step % 3;
                 const int kb = u >> 3, v = 2 * (u & 7);
-                if (part == 0) e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v], c_log2, -mc));
-                else if (part == 1) e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v + 1], c_log2, -mc));
-                else {
+                if (part == 0) {
+                    e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v], c_log2, -mc));
+                    pin(e0);
+                } else if (part == 1) {
+                    e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v + 1], c_log2, -mc));
+                    pin(e1);
+                } else {
                     bf16x2 pr;
                     pr[0] = (__bf16)e0;
                     pr[1] = (__bf16)e1;
+                    pin(pr);
                     pf[kb][v >> 3][v & 7] = pr[0];
                     pf[kb][v >> 3][(v & 7) + 1] = pr[1];
                 }
