@@ -82,12 +82,11 @@ __device__ inline float pair_sum(float x)
 // the VALU cannot overlap with MFMAs at all.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4v __attribute__((ext_vector_type(4)));
-__device__ inline f32x4 sum4_bf16(const bf16x8& p, int half, f32x4 acc)   // elements 4 half .. 4 half + 3 of p
+__device__ inline f32x4 sum4_bf16(uint32_t pair0, uint32_t pair1, f32x4 acc)   // two packed bf16 pairs
 {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     const s16x4v ones = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
-    bf16x4 q;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) q[e] = p[4 * half + e];
+    const u32x2 q = {pair0, pair1};
     return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones, __builtin_bit_cast(s16x4v, q), acc, 0, 0, 0);
 }
 
@@ -121,6 +120,16 @@ __device__ inline void pin(bf16x2& x)
     uint32_t u = __builtin_bit_cast(uint32_t, x);
     asm volatile("" : "+v"(u));
     x = __builtin_bit_cast(bf16x2, u);
+}
+
+// compile-time loop: f(integral_constant<int, I>) for I = BEGIN .. END-1
+template <int BEGIN, int END, class F>
+__device__ inline void static_for(F&& f)
+{
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
 }
 
 // in-page LDS row of a key: swap bits 2 and 3 of its index within the 16-key page
@@ -316,7 +325,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         f32x4 psum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            psum = sum4_bf16(p[u >> 2][(u >> 1) & 1], u & 1, psum);
+        {
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 w = __builtin_bit_cast(u32x4, p[u >> 2][(u >> 1) & 1]);
+            psum = sum4_bf16(w[2 * (u & 1)], w[2 * (u & 1) + 1], psum);
+        }
         l_run += psum[0];
     };
 
@@ -355,7 +368,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         __syncthreads();
 
         f32x16 sc[2][2];                                     // scores of tile i live in sc[i & 1]
-        bf16x8 pf[2][2];
 
         qk_tile(0, sc[0]);
         if (n_clear < 1) mask_tile(0, sc[0]);
@@ -378,28 +390,61 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             f32x16 (&s_cur)[2] = sc[R & 1];
             f32x16 (&s_nxt)[2] = sc[(R & 1) ^ 1];
             const float mc = m_run * c_log2;
-            float e0 = 0.f, e1 = 0.f;
             f32x4 psum = {0.f, 0.f, 0.f, 0.f};
-            // softmax work in 48 steps of two VALU instructions: unit u = steps 3u, 3u+1, 3u+2 turns scores
-            // 2u, 2u+1 (block u/8, registers 2(u%8), 2(u%8)+1) into a bf16 pair of P and adds it to l
-            auto softmax_step = [&](int step) {
-                const int u = step / 3, part = step % 3;
-                const int kb = u >> 3, v = 2 * (u & 7);
-                if (part == 0) {
-                    e0 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v], c_log2, -mc));
-                    pin(e0);
-                } else if (part == 1) {
-                    e1 = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][v + 1], c_log2, -mc));
-                    pin(e1);
+            // Softmax work on S(i): 16 units; unit u = 8 kb + 4 s + j turns scores 8s + 2j, 8s + 2j + 1 of
+            // key block kb into one register of the operand P[kb][s], with five instructions: F0 F1 (scale,
+            // subtract the maximum), E0 E1 (exp2), C (round the pair to bf16).  They are issued as a
+            // software-pipelined stream in which no instruction directly follows the one it depends on:
+            // group g is E0(g) E1(g) C(g-1) F0(g+1) F1(g+1), 90 slots in all, dealt evenly to slices 0..23.
+            uint32_t pw[2][2][4];
+            float fa[16], fb[16], ea[16], eb[16];
+            auto softmax_op = [&](auto idx_c) {
+                constexpr int idx = decltype(idx_c)::value;
+                constexpr int g = idx / 5, slot = idx % 5;
+                if constexpr (slot == 0) {
+                    if constexpr (g < 16) {
+                        ea[g] = __builtin_amdgcn_exp2f(fa[g]);
+                        pin(ea[g]);
+                    }
+                } else if constexpr (slot == 1) {
+                    if constexpr (g < 16) {
+                        eb[g] = __builtin_amdgcn_exp2f(fb[g]);
+                        pin(eb[g]);
+                    }
+                } else if constexpr (slot == 2) {
+                    constexpr int u = g - 1;
+                    if constexpr (u >= 0 && u < 16) {
+                        bf16x2 pr;
+                        pr[0] = (__bf16)ea[u];
+                        pr[1] = (__bf16)eb[u];
+                        pin(pr);
+                        pw[u >> 3][(u >> 2) & 1][u & 3] = __builtin_bit_cast(uint32_t, pr);
+                    }
                 } else {
-                    bf16x2 pr;
-                    pr[0] = (__bf16)e0;
-                    pr[1] = (__bf16)e1;
-                    pin(pr);
-                    pf[kb][v >> 3][v & 7] = pr[0];
-                    pf[kb][v >> 3][(v & 7) + 1] = pr[1];
+                    constexpr int u = g + 1;
+                    if constexpr (u < 16) {
+                        constexpr int kb = u >> 3, v = 2 * (u & 7) + (slot - 3);
+                        if constexpr (slot == 3) {
+                            fa[u] = fmaf(s_cur[kb][v], c_log2, -mc);
+                            pin(fa[u]);
+                        } else {
+                            fb[u] = fmaf(s_cur[kb][v], c_log2, -mc);
+                            pin(fb[u]);
+                        }
+                    }
                 }
             };
+            auto softmax_slice = [&](auto slice_c) {         // slice 0 .. 23 of the iteration
+                constexpr int sl = decltype(slice_c)::value;
+                static_for<(sl * 90) / 24, ((sl + 1) * 90) / 24>(softmax_op);
+            };
+            auto p_operand = [&](int kb, int sblk) -> bf16x8 {
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 t = {pw[kb][sblk][0], pw[kb][sblk][1], pw[kb][sblk][2], pw[kb][sblk][3]};
+                return __builtin_bit_cast(bf16x8, t);
+            };
+            fa[0] = fmaf(s_cur[0][0], c_log2, -mc);
+            fb[0] = fmaf(s_cur[0][1], c_log2, -mc);
             const int k_base = opaque(k_rd0), v_base = opaque(v_rd0);
             auto read_k = [&](int k) -> bf16x8 {             // operand of QK slice k: step k/2, key block k%2
                 return *(const bf16x8*)(smem + ((R + 1) & 3) * KV_BYTES + (k & 1) * 32 * 256 + (k_base ^ ((k >> 1) << 5)));
@@ -416,10 +461,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 #pragma unroll
             for (int k = 0; k < PF_DIST; ++k) opnd[k] = read_k(k);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                opnd[k + PF_DIST] = (k + PF_DIST < 16) ? read_k(k + PF_DIST) : read_v(k + PF_DIST - 16);
-                if (k < 2) {
+            static_for<0, 16>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                if constexpr (k + PF_DIST < 16) opnd[k + PF_DIST] = read_k(k + PF_DIST);
+                else opnd[k + PF_DIST] = read_v(k + PF_DIST - 16);
+                if constexpr (k < 2) {
                     f32x16 zero;
 #pragma unroll
                     for (int v = 0; v < 16; ++v) zero[v] = 0.f;
@@ -427,14 +473,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 } else {
                     s_nxt[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[k], qf[k >> 1], s_nxt[k & 1], 0, 0, 0);
                 }
-                softmax_step(2 * k);
-                softmax_step(2 * k + 1);
+                softmax_slice(kc);
                 // fetch the tiles that are first read two iterations from now (slots last read two
                 // iterations ago), once the matrix pipe has work queued
-                if (k == 2) load_k(i + 3, (R + 3) & 3);
-                if (k == 4) load_v(i + 2, (R + 2) & 3);
+                if constexpr (k == 2) load_k(i + 3, (R + 3) & 3);
+                if constexpr (k == 4) load_v(i + 2, (R + 2) & 3);
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
             // Mid-iteration publish point.  K(i+2) and V(i+1), fetched one iteration ago, must have landed
             // (the four loads issued above may stay in flight); the barrier makes them visible to all
             // waves well before iteration i+1 needs them, and sits where every wave still has MFMAs in
@@ -444,34 +489,34 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
             float mx = 0.f;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                if (k + PF_DIST < 16) opnd[16 + k + PF_DIST] = read_v(k + PF_DIST);
-                o_acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[16 + k], pf[k >> 3][(k >> 2) & 1],
+            static_for<0, 16>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                if constexpr (k + PF_DIST < 16) opnd[16 + k + PF_DIST] = read_v(k + PF_DIST);
+                o_acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[16 + k], p_operand(k >> 3, (k >> 2) & 1),
                                                                        o_acc[k & 3], 0, 0, 0);
-                if (k == 8 && needs_mask) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    mask_tile(i + 1, s_nxt);                 // before the maximum of S(i+1) is taken
-                    __builtin_amdgcn_sched_barrier(0);
+                if constexpr (k == 8) {
+                    if (needs_mask) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        mask_tile(i + 1, s_nxt);             // before the maximum of S(i+1) is taken
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
-                if (k < 8) {
-                    softmax_step(32 + 2 * k);
-                    softmax_step(32 + 2 * k + 1);
+                if constexpr (k < 8) {
+                    softmax_slice(std::integral_constant<int, 16 + k>{});
                 } else {
-                    // row maximum of S(i+1): 32 values, four per slice
-                    const int kb = (k - 8) >> 2, v = 4 * ((k - 8) & 3);
-                    // written as max(max(a, b), running) so that each pair costs one three-input maximum
-                    const float m2 = (k == 8) ? fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1])
-                                              : fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), mx);
+                    // row maximum of S(i+1): 32 values, four per slice, written as max(max(a, b), running)
+                    // so that each pair costs one three-input maximum
+                    constexpr int kb = (k - 8) >> 2, v = 4 * ((k - 8) & 3);
+                    float m2;
+                    if constexpr (k == 8) m2 = fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]);
+                    else m2 = fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), mx);
                     mx = fmaxf(fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]), m2);
-                }
-                if (k >= 8) {
                     // row sum of P(i), four values per slice, on the matrix pipe
-                    const int u = k - 8;
-                    psum = sum4_bf16(pf[u >> 2][(u >> 1) & 1], u & 1, psum);
+                    constexpr int u = k - 8;
+                    psum = sum4_bf16(pw[u >> 2][(u >> 1) & 1][2 * (u & 1)], pw[u >> 2][(u >> 1) & 1][2 * (u & 1) + 1], psum);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
             l_run += psum[0];
             mx = pair_max(mx);
             // The running maximum only has to keep exp2 in range, so it is raised (and O, l rescaled)
@@ -505,6 +550,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         if (i + 2 < n_tiles) iteration(i + 1, std::integral_constant<int, 1>{});
         if (i + 3 < n_tiles) iteration(i + 2, std::integral_constant<int, 2>{});
         // ---- tail: tile n-1
+        bf16x8 pf[2][2];
         switch ((n_tiles - 1) & 3) {
             case 0: exp_tile(sc[0], pf); pv_tile(0, pf); break;
             case 1: exp_tile(sc[1], pf); pv_tile(1, pf); break;
