@@ -86,8 +86,11 @@ typedef struct {
 emm_status emm_kv_scatter(const emm_batch *batch, const void *k_new, const void *v_new,
                           void *k_cache, void *v_cache, void *hip_stream);
 
-/* Bytes of device workspace emm_prefill_attn / emm_cross_attn need for this batch (may be 0).
- * Host-only; reads only the scalar fields. */
+/* Bytes of device workspace emm_prefill_attn / emm_cross_attn need for this batch (0 for EMM_F32, about
+ * 134 MB for EMM_BF16 whatever the batch).  The bf16 kernels cut the work units left over after an
+ * XCD's full rounds of 32 along the key axis, park the pieces' accumulators there and merge them with
+ * a second kernel on the same stream; the contents need no initialisation and mean nothing afterwards.
+ * Calls on different streams must not share a workspace.  Host-only; reads only the scalar fields. */
 emm_status emm_prefill_attn_workspace_size(const emm_batch *batch, size_t *bytes);
 
 /*
@@ -98,7 +101,8 @@ emm_status emm_prefill_attn_workspace_size(const emm_batch *batch, size_t *bytes
  *   q       device, read,  [T][H][d]
  *   out     device, write, [T][H][d], same dtype as q (bf16 rounded to nearest even)
  *   lse     device, write, [T][H] fp32 natural-log softmax denominators, or NULL
- *   workspace  device scratch of at least emm_prefill_attn_workspace_size bytes (may be NULL if 0)
+ *   workspace  device scratch of at least emm_prefill_attn_workspace_size bytes, 16-byte aligned (may be
+ *              NULL if that size is 0); EMM_ERR_NULL / EMM_ERR_WORKSPACE if missing / too small
  * bf16 path: scores and both products accumulate in fp32, softmax weights are rounded to bf16 for
  * the value product.  Results are run-to-run bitwise deterministic.
  */

@@ -94,6 +94,7 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     args.out = out;
     args.lse = lse;
     args.causal = causal;
+    args.workspace = need > 0 ? workspace : nullptr;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t err = (b->dtype == EMM_BF16) ? emm::launch_attn_bf16_d128(args, stream)
                                                   : emm::launch_attn_f32(args, stream);
@@ -130,7 +131,10 @@ emm_status emm_prefill_attn_workspace_size(const emm_batch* b, size_t* bytes)
     *bytes = 0;
     emm_status st = check_scalars(b);
     if (st != EMM_OK) return st;
-    return check_supported(b);
+    st = check_supported(b);
+    if (st != EMM_OK) return st;
+    if (b->dtype == EMM_BF16) *bytes = emm::attn_bf16_d128_workspace_bytes();
+    return EMM_OK;
 }
 
 emm_status emm_prefill_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,

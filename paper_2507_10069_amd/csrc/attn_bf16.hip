@@ -135,8 +135,126 @@ __device__ inline void static_for(F&& f)
 // in-page LDS row of a key: swap bits 2 and 3 of its index within the 16-key page
 __device__ inline int swap23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1); }
 
+// ---- Work units, and cutting the last ones along the key axis.
+// A unit is one row tile of one (request, KV head) pair.  An XCD works through its units in launch order on
+// its 32 compute units, so with U units the last U mod 32 of them run in a final, partly empty round.  When
+// a workspace is given, each of those tail units is cut into 2 or 4 pieces of equal key range, done by
+// separate workgroups, so that the final round fills the XCD; a piece writes its unnormalised accumulator,
+// running maximum and row sum to the workspace and a second, small kernel merges the pieces of a unit.
+// Which units are cut follows from the batch's lengths alone, so every workgroup of either kernel derives
+// the same plan by itself: no flags, counters or descriptors are exchanged.
+constexpr int CU_PER_XCD = 32;
+constexpr int MAX_PARTS = 4;
+constexpr int MAX_TAIL = CU_PER_XCD - 1;                 // tail units per XCD
+constexpr int MIN_TILES_PER_PART = 16;                   // shorter units are not worth cutting
+constexpr int SPLIT_MAX_PAIRS_PER_XCD = 32;              // planning scans an XCD's pairs: keep that short
+constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
+
+struct LaunchShape {
+    int n_row_tiles;        // row tiles of the longest request
+    int n_pairs;            // (request, KV head) pairs in the batch
+    int pairs_per_xcd;      // ceil(n_pairs / 8)
+    int split;              // 1: tail units may be cut (workspace present)
+};
+
+struct UnitPlan {
+    int pair, tile;         // pair < 0: this workgroup has nothing to do
+    int parts, part;        // the unit's key tiles are cut into `parts` ranges; this workgroup does range `part`
+    int slot;               // tail slot of the unit within its XCD (meaningful when parts > 1)
+};
+
+__host__ __device__ inline int split_factor_of(int rem)  // pieces per tail unit when rem units are left over
+{
+    // With more leftover units the compute units that stay idle in the last round are few, and the busy
+    // ones run at a higher clock for it (the chip is power limited): cutting then costs more than it gains.
+    if (rem == 0 || rem > 12) return 1;
+    return rem > 8 ? 2 : 4;
+}
+__device__ inline int split_factor(int rem) { return split_factor_of(rem); }
+inline int host_split_factor(int rem) { return split_factor_of(rem); }
+
+__device__ inline int wave_sum32(int x)                  // sum over lanes 0..31 (and, separately, 32..63)
+{
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) x += __shfl_xor(x, d, 64);
+    return x;
+}
+
+// Plan of workgroup `in_xcd` of XCD `xcd`.  Regular workgroups come first (pair-major, row tiles descending,
+// as many slots per pair as the longest request needs), then 3 x 31 workgroups for pieces 1..3 of tail units.
+// The scan over the XCD's pairs (at most 32 when cutting is enabled) is done by the lanes of each wave.
+__device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd)
+{
+    UnitPlan u;
+    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0;
+    const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
+    const bool regular = in_xcd < n_regular;
+    const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
+    int my_cnt = 0;
+    if (regular) {
+        const int pair = xcd + NUM_XCD * my_pi;
+        if (pair >= L.n_pairs) return u;
+        const int tile = L.n_row_tiles - 1 - in_xcd % L.n_row_tiles;
+        my_cnt = (b.new_lens[pair / b.num_kv_heads] * G + BR - 1) / BR;
+        if (tile >= my_cnt) return u;                    // most workgroups of a ragged batch leave here
+        u.pair = pair;
+        u.tile = tile;
+        if (!L.split) return u;
+    } else if (!L.split) {
+        return u;
+    }
+    // lane pi (mod 32) looks at pair xcd + 8 pi
+    const int pi = threadIdx.x & 31;
+    const int lane_pair = xcd + NUM_XCD * pi;
+    const int cnt = (pi < L.pairs_per_xcd && lane_pair < L.n_pairs)
+                        ? (b.new_lens[lane_pair / b.num_kv_heads] * G + BR - 1) / BR : 0;
+    const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
+    const int rem = total % CU_PER_XCD;
+    const int parts = split_factor(rem);
+    if (parts == 1) return u;                            // regular: whole unit; extra: nothing to do (pair < 0)
+    const int first_tail = total - rem;
+    if (regular) {
+        const int before_mine = __builtin_amdgcn_readfirstlane(wave_sum32(pi < my_pi ? cnt : 0));
+        const int ordinal = before_mine + my_cnt - 1 - u.tile;
+        if (ordinal >= first_tail) {
+            u.parts = parts;
+            u.slot = ordinal - first_tail;
+        }
+        return u;
+    }
+    const int e = in_xcd - n_regular;
+    const int slot = e / (MAX_PARTS - 1), part = 1 + e % (MAX_PARTS - 1);
+    if (slot >= rem || part >= parts) return u;
+    const int ordinal = first_tail + slot;
+    // the pair that holds this ordinal: the first one whose inclusive running count exceeds it
+    int incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) {
+        const int up = __shfl_up(incl, d, 32);
+        if (pi >= d) incl += up;
+    }
+    const unsigned long long hit = __builtin_amdgcn_ballot_w64(incl > ordinal) & 0xffffffffull;
+    if (hit == 0) return u;
+    const int hit_pi = __builtin_ctzll(hit);
+    const int hit_incl = __builtin_amdgcn_readlane(incl, hit_pi);
+    const int hit_cnt = __builtin_amdgcn_readlane(cnt, hit_pi);
+    u.pair = xcd + NUM_XCD * hit_pi;
+    u.tile = hit_incl - 1 - ordinal;                     // = cnt - 1 - (ordinal - exclusive count)
+    (void)hit_cnt;
+    u.parts = parts;
+    u.part = part;
+    u.slot = slot;
+    return u;
+}
+
+// workspace of pieces: [xcd][tail slot][piece][66][512] floats
+__device__ inline float* part_base(void* workspace, int xcd, int slot, int part)
+{
+    return (float*)workspace + (size_t)((xcd * MAX_TAIL + slot) * MAX_PARTS + part) * PART_FLOATS;
+}
+
 template <bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a, int n_row_tiles, int n_pairs)
+__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a, LaunchShape L)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * KV_BYTES];   // K ring, then V ring
     constexpr int V_SM = NBUF * KV_BYTES;                    // byte offset of the V buffers
@@ -149,9 +267,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // stream the same pages through its L2.
     const int G = b.num_q_heads / b.num_kv_heads;
     const int xcd = blockIdx.x % NUM_XCD, in_xcd = blockIdx.x / NUM_XCD;
-    const int pair = xcd + NUM_XCD * (in_xcd / n_row_tiles);
-    if (pair >= n_pairs) return;
-    const int tile = n_row_tiles - 1 - in_xcd % n_row_tiles;
+    UnitPlan plan = plan_unit(b, G, L, xcd, in_xcd);
+    if (plan.pair < 0) return;
+    const int pair = plan.pair, tile = plan.tile;
     const int kvh = pair % b.num_kv_heads;
     const int r = pair / b.num_kv_heads;
 
@@ -163,7 +281,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int ctx_len = CAUSAL ? P + N : P;                  // slots of this request that hold tokens
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = CAUSAL ? P + last_row / G + 1 : P;    // keys this row tile can see
-    const int n_tiles = (kv_len + BC - 1) / BC;
+    const int n_tiles_unit = (kv_len + BC - 1) / BC;
+    // a unit too short to be worth cutting is done whole by its regular workgroup
+    if (plan.parts > 1 && n_tiles_unit < MIN_TILES_PER_PART * plan.parts) {
+        if (plan.part > 0) return;
+        plan.parts = 1;
+    }
+    // this workgroup's key tiles: t_begin .. t_begin + n_tiles - 1.  Every piece of a cut unit starts with a
+    // tile all of whose keys every row sees (the unit has at least 16 tiles per piece and a row tile spans
+    // at most 256 tokens), so the first row maximum is finite in every piece.
+    const int t_begin = plan.part * n_tiles_unit / plan.parts;
+    const int n_tiles = (plan.part + 1) * n_tiles_unit / plan.parts - t_begin;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -356,22 +484,23 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     };
 
     if (n_tiles > 0) {
-        // ---- prologue: K(0), V(0), K(1), V(1), K(2) on their way to LDS
-        refill_pages(0);
-        load_k(0, 0);
-        load_v(0, 0);
-        load_k(1, 1);
-        load_v(1, 1);
-        load_k(2, 2);
+        // ---- prologue: the first tiles K(0), V(0), K(1), V(1), K(2) of this workgroup's range on their way
+        //      to LDS (tile numbers in the comments below are relative to t_begin; ring slots follow them)
+        refill_pages(t_begin);
+        load_k(t_begin, 0);
+        load_v(t_begin, 0);
+        load_k(t_begin + 1, 1);
+        load_v(t_begin + 1, 1);
+        load_k(t_begin + 2, 2);
         __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0): this wave's rows have landed
-        zero_v_tail(0, 0);
+        zero_v_tail(t_begin, 0);
         __syncthreads();
 
         f32x16 sc[2][2];                                     // scores of tile i live in sc[i & 1]
 
         qk_tile(0, sc[0]);
-        if (n_clear < 1) mask_tile(0, sc[0]);
-        m_run = row_max(sc[0]);                              // finite: key 0 is visible to every row
+        if (t_begin >= n_clear) mask_tile(t_begin, sc[0]);
+        m_run = row_max(sc[0]);                              // finite: every row sees a key of the first tile
 
         // Iteration i (R = i % 4 fixed at compile time so that buffer offsets and register roles are
         // static).  K(i+1) is in K slot (R+1)%4, V(i) in V slot R, S(i) in sc[R & 1].  The tiles fetched
@@ -537,8 +666,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         };
         // four tiles per trip, straight-line (a tile's ring slot is its position in the body), then up to
         // three more; every wave runs n_tiles-1 iterations, one barrier each
-        int i = 0;
-        for (; i + 4 < n_tiles; i += 4) {
+        // (iteration() takes the absolute tile number; the ring slot is the position relative to t_begin)
+        int i = t_begin;
+        const int t_end = t_begin + n_tiles;
+        for (; i + 4 < t_end; i += 4) {
             if (i + 6 - pg_base >= 64) refill_pages(i + 2);  // tiles i+2 .. i+6 are fetched in this trip
             iteration(i, std::integral_constant<int, 0>{});
             iteration(i + 1, std::integral_constant<int, 1>{});
@@ -546,9 +677,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             iteration(i + 3, std::integral_constant<int, 3>{});
         }
         if (i + 5 - pg_base >= 64) refill_pages(i + 2);      // the leftover iterations fetch tiles i+2 .. i+5
-        if (i + 1 < n_tiles) iteration(i, std::integral_constant<int, 0>{});
-        if (i + 2 < n_tiles) iteration(i + 1, std::integral_constant<int, 1>{});
-        if (i + 3 < n_tiles) iteration(i + 2, std::integral_constant<int, 2>{});
+        if (i + 1 < t_end) iteration(i, std::integral_constant<int, 0>{});
+        if (i + 2 < t_end) iteration(i + 1, std::integral_constant<int, 1>{});
+        if (i + 3 < t_end) iteration(i + 2, std::integral_constant<int, 2>{});
         // ---- tail: tile n-1
         bf16x8 pf[2][2];
         switch ((n_tiles - 1) & 3) {
@@ -564,6 +695,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     {
         int t2 = threadIdx.x;
         asm volatile("" : "+v"(t2));
+        if (plan.parts > 1) {
+            // a piece of a cut unit: unnormalised accumulator, running maximum and row sum go to the
+            // workspace, one coalesced row of 512 floats per register; attn_bf16_merge_kernel finishes
+            float* __restrict__ ws = part_base(a.workspace, xcd, plan.slot, plan.part) + t2;
+            const float l_part = pair_sum(l_run);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) ws[(16 * nb + v) * NTHREADS] = o_acc[nb][v];
+            ws[64 * NTHREADS] = m_run;
+            ws[65 * NTHREADS] = l_part;
+            return;
+        }
         const int e_l32 = t2 & 31, e_h32 = (t2 >> 5) & 1;
         const int e_row = row0 + (t2 >> 6) * 32 + e_l32;
         if (e_row >= n_rows) return;
@@ -589,7 +733,79 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     }
 }
 
+// Merges the pieces of the cut units: one workgroup per (XCD, tail slot), thread for thread the layout of
+// the main kernel's epilogue.  Workgroups whose slot holds no cut unit leave at once.
+__global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, LaunchShape L)
+{
+    const BatchView& b = a.b;
+    const int G = b.num_q_heads / b.num_kv_heads;
+    const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
+    // the plan of the workgroup that did piece 1 of this slot names the unit
+    const UnitPlan plan = plan_unit(b, G, L, xcd, L.pairs_per_xcd * L.n_row_tiles + slot * (MAX_PARTS - 1));
+    if (plan.pair < 0) return;
+    const int kvh = plan.pair % b.num_kv_heads;
+    const int r = plan.pair / b.num_kv_heads;
+    const int N = b.new_lens[r];
+    const int n_rows = N * G;
+    const int row0 = plan.tile * BR;
+    const int P = b.prefix_lens[r];
+    const int last_row = min(row0 + BR - 1, n_rows - 1);
+    const int kv_len = a.causal ? P + last_row / G + 1 : P;
+    if ((kv_len + BC - 1) / BC < MIN_TILES_PER_PART * plan.parts) return;   // the unit was done whole
+
+    const int tid = threadIdx.x;
+    const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
+    const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, 0) + tid;
+    float m_part[MAX_PARTS], w[MAX_PARTS];
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < MAX_PARTS; ++j) {
+        m_part[j] = (j < plan.parts) ? ws0[(size_t)j * PART_FLOATS + 64 * NTHREADS] : -INFINITY;
+        m_all = fmaxf(m_all, m_part[j]);
+    }
+    float l_tot = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAX_PARTS; ++j) {
+        w[j] = (j < plan.parts) ? __builtin_amdgcn_exp2f((m_part[j] - m_all) * c_log2) : 0.f;
+        if (j < plan.parts) l_tot += w[j] * ws0[(size_t)j * PART_FLOATS + 65 * NTHREADS];
+    }
+    const int l32 = tid & 31, h32 = (tid >> 5) & 1;
+    const int row = row0 + (tid >> 6) * 32 + l32;
+    if (row >= n_rows) return;
+    const int tok = row / G;
+    const int hq = kvh * G + (row - tok * G);
+    const long long q_row = (long long)b.cu_new_lens[r] + tok;
+    const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
+    __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        float acc[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+        for (int j = 0; j < MAX_PARTS; ++j)
+            if (j < plan.parts) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] += w[j] * ws0[(size_t)j * PART_FLOATS + (16 * nb + v) * NTHREADS];
+            }
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[4 * v4 + e] * inv);
+            *(bf16x4*)(op + 32 * nb + 8 * v4 + 4 * h32) = o;
+        }
+    }
+    if (a.lse != nullptr && h32 == 0)
+        a.lse[q_row * b.num_q_heads + hq] = (l_tot > 0.f) ? m_all * b.softmax_scale + logf(l_tot) : -INFINITY;
+}
+
 }  // namespace
+
+size_t attn_bf16_d128_workspace_bytes()
+{
+    return (size_t)NUM_XCD * MAX_TAIL * MAX_PARTS * PART_FLOATS * sizeof(float);
+}
 
 hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
 {
@@ -600,14 +816,31 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     const long long n_row_tiles = (max_rows + BR - 1) / BR;
     const long long n_pairs = (long long)b.num_reqs * b.num_kv_heads;
     const long long pairs_per_xcd = (n_pairs + NUM_XCD - 1) / NUM_XCD;
-    const long long grid = NUM_XCD * pairs_per_xcd * n_row_tiles;
+    LaunchShape L;
+    L.n_row_tiles = (int)n_row_tiles;
+    L.n_pairs = (int)n_pairs;
+    L.pairs_per_xcd = (int)pairs_per_xcd;
+    L.split = (a.workspace != nullptr && pairs_per_xcd <= SPLIT_MAX_PAIRS_PER_XCD) ? 1 : 0;
+    if (L.split && (long long)b.num_reqs * b.max_new_len == b.total_new_tokens) {
+        // every request has max_new_len new tokens, so the host knows each XCD's unit count and can tell
+        // whether any tail unit would be cut at all; if none, the extra workgroups and the merge launch go
+        bool any = false;
+        for (int x = 0; x < NUM_XCD && x < n_pairs; ++x) {
+            const long long pairs_here = (n_pairs - x + NUM_XCD - 1) / NUM_XCD;
+            any = any || host_split_factor((int)((pairs_here * n_row_tiles) % CU_PER_XCD)) > 1;
+        }
+        if (!any) L.split = 0;
+    }
+    const long long per_xcd = pairs_per_xcd * n_row_tiles + (L.split ? MAX_TAIL * (MAX_PARTS - 1) : 0);
+    const long long grid = NUM_XCD * per_xcd;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)
-        hipLaunchKernelGGL(attn_bf16_d128_kernel<true>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a,
-                           (int)n_row_tiles, (int)n_pairs);
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<true>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, L);
     else
-        hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a,
-                           (int)n_row_tiles, (int)n_pairs);
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, L);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || !L.split) return err;
+    hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * MAX_TAIL), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }
 

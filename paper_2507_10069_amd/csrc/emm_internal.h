@@ -26,6 +26,7 @@ struct AttnArgs {
     void* out;            // [T][H][d]
     float* lse;           // [T][H] or nullptr
     int32_t causal;       // 1: keys 0..P+j ; 0: keys 0..P-1
+    void* workspace;      // scratch for the bf16 kernel's cut units, or nullptr
 };
 
 // Each launcher enqueues on `stream` and returns the launch status.
@@ -33,5 +34,6 @@ hipError_t launch_kv_scatter(const BatchView& b, const void* k_new, const void* 
                              void* v_cache, int elt_bytes, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream);
+size_t attn_bf16_d128_workspace_bytes();   // what launch_attn_bf16_d128 wants behind AttnArgs::workspace
 
 }  // namespace emm

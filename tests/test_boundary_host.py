@@ -40,7 +40,8 @@ def test_struct_layout_matches_header():
 
 
 def test_workspace_size_and_scalar_checks():
-    assert B.emm_prefill_attn_workspace_size(_batch()) >= 0
+    assert B.emm_prefill_attn_workspace_size(_batch()) > 0
+    assert B.emm_prefill_attn_workspace_size(_batch(dtype="f32")) == 0
     lib = B.load()
     n = ctypes.c_size_t()
     assert lib.emm_prefill_attn_workspace_size(None, ctypes.byref(n)) == B.EMM_ERR_NULL
@@ -65,9 +66,14 @@ def test_attention_rejects_before_launch(entry):
     assert fn(ctypes.byref(b), ok, ok, ok, ok, None, None, 0, None) == B.EMM_ERR_NULL
     b = _batch()
     b.page_table = b.prefix_lens = b.new_lens = b.cu_new_lens = ok
-    assert fn(ctypes.byref(b), None, ok, ok, ok, None, None, 0, None) == B.EMM_ERR_NULL
-    assert fn(ctypes.byref(b), ok + 8, ok, ok, ok, None, None, 0, None) == B.EMM_ERR_INVALID_ARG
-    assert fn(ctypes.byref(b), ok, ok, ok, ok, ok + 2, None, 0, None) == B.EMM_ERR_INVALID_ARG
+    need = B.emm_prefill_attn_workspace_size(b)
+    assert need > 0                  # the bf16 kernels cut their last work units and merge them through it
+    assert fn(ctypes.byref(b), None, ok, ok, ok, None, ok, need, None) == B.EMM_ERR_NULL
+    assert fn(ctypes.byref(b), ok + 8, ok, ok, ok, None, ok, need, None) == B.EMM_ERR_INVALID_ARG
+    assert fn(ctypes.byref(b), ok, ok, ok, ok, ok + 2, ok, need, None) == B.EMM_ERR_INVALID_ARG
+    assert fn(ctypes.byref(b), ok, ok, ok, ok, None, None, need, None) == B.EMM_ERR_NULL
+    assert fn(ctypes.byref(b), ok, ok, ok, ok, None, ok, need - 1, None) == B.EMM_ERR_WORKSPACE
+    assert fn(ctypes.byref(b), ok, ok, ok, ok, None, ok + 4, need, None) == B.EMM_ERR_INVALID_ARG
     assert fn(None, ok, ok, ok, ok, None, None, 0, None) == B.EMM_ERR_NULL
     # empty batches are no-ops that never reach a launch
     assert fn(ctypes.byref(_batch(num_reqs=0, total_new_tokens=0, max_new_len=0)), None, None, None, None,

@@ -111,6 +111,35 @@ def test_ragged_cross_sweep():
     assert (out[:5] == 0).all()
 
 
+# Batches whose last work units are cut along the key axis and merged by the second kernel.  A unit is a
+# 256-row tile of one (request, KV head) pair; pairs are dealt to the 8 XCDs; the units an XCD has left over
+# after its full rounds of 32 are cut into 4 pieces (1..8 left over) or 2 (9..12) when they are long enough.
+CUT_CASES = [
+    # name, kind, H, Hkv, prefix lens, new lens
+    ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 2 units per XCD on 4 XCDs, 4 pieces each
+    ("cut2_causal", "causal", 28, 4, [2100], [350]),                # 10 units per XCD, 2 pieces each
+    ("cut4_cross", "cross", 32, 8, [6404, 6404], [100, 37]),        # 3 units per XCD, 4 pieces; ragged last tile
+    ("cut_mixed", "causal", 16, 8, [8000, 100, 4100], [64, 200, 3]),  # long units are cut, short ones are not
+    ("cut_edge", "causal", 8, 8, [4032 - 5, 4096 - 5], [5, 5]),     # 63 and 64 key tiles: just below / at the bar
+    ("cut_gqa1", "causal", 8, 8, [4100], [300]),                    # one head per group: 256 tokens per row tile
+]
+
+
+@pytest.mark.parametrize("name,kind,H,Hkv,prefix,new", CUT_CASES)
+def test_cut_units_parity(name, kind, H, Hkv, prefix, new):
+    print("case", name, flush=True)
+    wl = W.build_workload(name, kind, "bf16", 950 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=prefix, new_lens=new)
+    dw = _gpu_run(wl)
+    tokens = None if wl.total_new_tokens <= 160 else _sample_tokens(wl, 96, seed=len(name))
+    print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
+    # a second launch on the same workspace (stale pieces of the first) gives the same bits
+    first = B.DeviceWorkload.to_numpy_bits(dw.out).tobytes()
+    dw.attention()
+    torch.cuda.synchronize()
+    assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
