@@ -438,9 +438,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // log2(e) * scale, wave-uniform: kept in a scalar register
     const float c_log2 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
         __builtin_bit_cast(int, b.softmax_scale * 1.44269504088896340736f)));
+    const float slack = RESCALE_LOG2 / c_log2;               // the lag allowed to the running maximum, in score units
 
     // P = exp2(S c - m c) rounded to bf16; l accumulates the rounded values (the same numbers the value
-    // product uses) with one dot-product instruction per pair
+    // product uses), four at a time on the matrix pipe
     auto exp_tile = [&](const f32x16 (&s)[2], bf16x8 (&p)[2][2]) {
         const float mc = m_run * c_log2;
 #pragma unroll
@@ -647,14 +648,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 __builtin_amdgcn_sched_barrier(0);
             });
             l_run += psum[0];
-            mx = pair_max(mx);
             // The running maximum only has to keep exp2 in range, so it is raised (and O, l rescaled)
-            // only when a row's new maximum exceeds it by more than 2^RESCALE_LOG2.  Both lanes of a row
-            // hold the same m_run and the same maximum, so they decide alike.
-            const float m_cand = fmaxf(m_run, mx);
-            const bool raise = (m_cand - m_run) * c_log2 > RESCALE_LOG2;
-            if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-                const float m_new = raise ? m_cand : m_run;
+            // only when a row's new maximum exceeds it by more than 2^RESCALE_LOG2.  The common case costs
+            // one compare of this lane's half-row maximum against m_run + slack; only when some lane of the
+            // wave is over are the two halves of a row combined (both lanes of a row then decide alike).
+            if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {
+                mx = pair_max(mx);
+                const float m_new = (mx > m_run + slack) ? mx : m_run;
                 const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
                 l_run *= alpha;
                 m_run = m_new;
