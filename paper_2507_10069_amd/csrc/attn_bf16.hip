@@ -150,11 +150,14 @@ constexpr int MIN_TILES_PER_PART = 16;                   // shorter units are no
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 32;              // planning scans an XCD's pairs: keep that short
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
 
+// With fewer than 8 (request, KV head) pairs some XCDs would get no work, so each pair is dealt to `fan`
+// XCDs: sub-pair pair * fan + j owns the row tiles j, j + fan, j + 2 fan, ...  "Pair" below means sub-pair.
 struct LaunchShape {
-    int n_row_tiles;        // row tiles of the longest request
-    int n_pairs;            // (request, KV head) pairs in the batch
+    int n_row_tiles;        // row tiles of the longest request's sub-pairs
+    int n_pairs;            // sub-pairs in the batch
     int pairs_per_xcd;      // ceil(n_pairs / 8)
     int split;              // 1: tail units may be cut (workspace present)
+    int fan;                // sub-pairs per (request, KV head) pair: 1, 2, 4 or 8
 };
 
 struct UnitPlan {
@@ -173,6 +176,13 @@ __host__ __device__ inline int split_factor_of(int rem)  // pieces per tail unit
 __device__ inline int split_factor(int rem) { return split_factor_of(rem); }
 inline int host_split_factor(int rem) { return split_factor_of(rem); }
 
+// row tiles (units) of sub-pair sp
+__host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int sp)
+{
+    const int cnt = (new_len * G + BR - 1) / BR, j = sp % fan;
+    return cnt > j ? (cnt - j + fan - 1) / fan : 0;
+}
+
 __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31 (and, separately, 32..63)
 {
 #pragma unroll
@@ -190,24 +200,25 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
     const bool regular = in_xcd < n_regular;
     const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
-    int my_cnt = 0;
+    int my_cnt = 0, my_idx = 0;
     if (regular) {
-        const int pair = xcd + NUM_XCD * my_pi;
-        if (pair >= L.n_pairs) return u;
-        const int tile = L.n_row_tiles - 1 - in_xcd % L.n_row_tiles;
-        my_cnt = (b.new_lens[pair / b.num_kv_heads] * G + BR - 1) / BR;
-        if (tile >= my_cnt) return u;                    // most workgroups of a ragged batch leave here
-        u.pair = pair;
-        u.tile = tile;
+        const int sp = xcd + NUM_XCD * my_pi;
+        if (sp >= L.n_pairs) return u;
+        const int idx = L.n_row_tiles - 1 - in_xcd % L.n_row_tiles;      // position among the sub-pair's tiles
+        my_cnt = sub_pair_tiles(b.new_lens[sp / L.fan / b.num_kv_heads], G, L.fan, sp);
+        if (idx >= my_cnt) return u;                     // most workgroups of a ragged batch leave here
+        u.pair = sp / L.fan;
+        u.tile = sp % L.fan + L.fan * idx;
+        my_idx = idx;
         if (!L.split) return u;
     } else if (!L.split) {
         return u;
     }
     // lane pi (mod 32) looks at pair xcd + 8 pi
     const int pi = threadIdx.x & 31;
-    const int lane_pair = xcd + NUM_XCD * pi;
-    const int cnt = (pi < L.pairs_per_xcd && lane_pair < L.n_pairs)
-                        ? (b.new_lens[lane_pair / b.num_kv_heads] * G + BR - 1) / BR : 0;
+    const int lane_sp = xcd + NUM_XCD * pi;
+    const int cnt = (pi < L.pairs_per_xcd && lane_sp < L.n_pairs)
+                        ? sub_pair_tiles(b.new_lens[lane_sp / L.fan / b.num_kv_heads], G, L.fan, lane_sp) : 0;
     const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
     const int rem = total % CU_PER_XCD;
     const int parts = split_factor(rem);
@@ -215,7 +226,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int first_tail = total - rem;
     if (regular) {
         const int before_mine = __builtin_amdgcn_readfirstlane(wave_sum32(pi < my_pi ? cnt : 0));
-        const int ordinal = before_mine + my_cnt - 1 - u.tile;
+        const int ordinal = before_mine + my_cnt - 1 - my_idx;
         if (ordinal >= first_tail) {
             u.parts = parts;
             u.slot = ordinal - first_tail;
@@ -237,10 +248,9 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     if (hit == 0) return u;
     const int hit_pi = __builtin_ctzll(hit);
     const int hit_incl = __builtin_amdgcn_readlane(incl, hit_pi);
-    const int hit_cnt = __builtin_amdgcn_readlane(cnt, hit_pi);
-    u.pair = xcd + NUM_XCD * hit_pi;
-    u.tile = hit_incl - 1 - ordinal;                     // = cnt - 1 - (ordinal - exclusive count)
-    (void)hit_cnt;
+    const int hit_sp = xcd + NUM_XCD * hit_pi;
+    u.pair = hit_sp / L.fan;
+    u.tile = hit_sp % L.fan + L.fan * (hit_incl - 1 - ordinal);   // position = cnt - 1 - (ordinal - exclusive count)
     u.parts = parts;
     u.part = part;
     u.slot = slot;
@@ -264,7 +274,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // round-robin as well -- the KV heads of one request cost the same, so this balances the XCDs whatever
     // the request lengths are -- and an XCD works through its pairs one after the other, row tiles from
     // the last (longest key range) to the first, so that the workgroups running together on an XCD mostly
-    // stream the same pages through its L2.
+    // stream the same pages through its L2.  plan_unit() says which unit, and which part of its key range,
+    // this workgroup does.
     const int G = b.num_q_heads / b.num_kv_heads;
     const int xcd = blockIdx.x % NUM_XCD, in_xcd = blockIdx.x / NUM_XCD;
     UnitPlan plan = plan_unit(b, G, L, xcd, in_xcd);
@@ -813,21 +824,27 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     if (b.total_new_tokens == 0 || b.num_reqs == 0) return hipSuccess;
     const int G = b.num_q_heads / b.num_kv_heads;
     const long long max_rows = (long long)b.max_new_len * G;
-    const long long n_row_tiles = (max_rows + BR - 1) / BR;
-    const long long n_pairs = (long long)b.num_reqs * b.num_kv_heads;
+    const long long n_pair_tiles = (max_rows + BR - 1) / BR;
+    const long long n_real_pairs = (long long)b.num_reqs * b.num_kv_heads;
+    int fan = 1;
+    while (fan < NUM_XCD && n_real_pairs * fan * 2 <= NUM_XCD) fan *= 2;
+    const long long n_pairs = n_real_pairs * fan;                        // sub-pairs
+    const long long n_row_tiles = (n_pair_tiles + fan - 1) / fan;        // per sub-pair
     const long long pairs_per_xcd = (n_pairs + NUM_XCD - 1) / NUM_XCD;
     LaunchShape L;
     L.n_row_tiles = (int)n_row_tiles;
     L.n_pairs = (int)n_pairs;
     L.pairs_per_xcd = (int)pairs_per_xcd;
+    L.fan = fan;
     L.split = (a.workspace != nullptr && pairs_per_xcd <= SPLIT_MAX_PAIRS_PER_XCD) ? 1 : 0;
     if (L.split && (long long)b.num_reqs * b.max_new_len == b.total_new_tokens) {
         // every request has max_new_len new tokens, so the host knows each XCD's unit count and can tell
         // whether any tail unit would be cut at all; if none, the extra workgroups and the merge launch go
         bool any = false;
-        for (int x = 0; x < NUM_XCD && x < n_pairs; ++x) {
-            const long long pairs_here = (n_pairs - x + NUM_XCD - 1) / NUM_XCD;
-            any = any || host_split_factor((int)((pairs_here * n_row_tiles) % CU_PER_XCD)) > 1;
+        for (int x = 0; x < NUM_XCD; ++x) {
+            long long units = 0;
+            for (long long sp = x; sp < n_pairs; sp += NUM_XCD) units += sub_pair_tiles(b.max_new_len, G, fan, (int)sp);
+            any = any || host_split_factor((int)(units % CU_PER_XCD)) > 1;
         }
         if (!any) L.split = 0;
     }

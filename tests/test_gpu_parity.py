@@ -140,6 +140,18 @@ def test_cut_units_parity(name, kind, H, Hkv, prefix, new):
     assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
 
 
+@pytest.mark.parametrize("H,Hkv,prefix,new", [(4, 1, [300], [700]), (8, 2, [0], [1500]), (6, 1, [70, 0, 513], [300, 90, 64]),
+                                              (8, 4, [129], [1]), (2, 1, [5000], [1100])])
+def test_few_pairs_spread_over_xcds(H, Hkv, prefix, new):
+    """Fewer than 8 (request, KV head) pairs: each pair's row tiles are dealt to several XCDs."""
+    print("case few pairs", H, Hkv, prefix, new, flush=True)
+    wl = W.build_workload("few_pairs", "causal", "bf16", 990 + H, num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=prefix, new_lens=new)
+    dw = _gpu_run(wl)
+    tokens = None if wl.total_new_tokens <= 200 else _sample_tokens(wl, 128, seed=H)
+    print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
