@@ -146,7 +146,7 @@ __device__ inline int swap23(int x) { return (x & ~12) | ((x & 4) << 1) | ((x & 
 constexpr int CU_PER_XCD = 32;
 constexpr int MAX_PARTS = 4;
 constexpr int MAX_TAIL = CU_PER_XCD - 1;                 // tail units per XCD
-constexpr int MIN_TILES_PER_PART = 16;                   // shorter units are not worth cutting
+constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 32;              // planning scans an XCD's pairs: keep that short
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
 
@@ -181,6 +181,16 @@ __host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int s
 {
     const int cnt = (new_len * G + BR - 1) / BR, j = sp % fan;
     return cnt > j ? (cnt - j + fan - 1) / fan : 0;
+}
+
+// May a unit of n_tiles key tiles be cut into `parts` pieces?  Every piece must have MIN_TILES_PER_PART
+// tiles, and the first tile of every piece must lie wholly at or below limit_min, the last key that the
+// unit's first row sees: then each row finds a visible key in the first tile of each piece and its
+// running maximum starts finite.  (Rows only see more keys further down the tile.)
+__device__ inline bool cuttable(int n_tiles, int parts, int limit_min)
+{
+    const int last_begin = (parts - 1) * n_tiles / parts;
+    return n_tiles >= MIN_TILES_PER_PART * parts && (last_begin + 1) * BC - 1 <= limit_min;
 }
 
 __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31 (and, separately, 32..63)
@@ -293,14 +303,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = CAUSAL ? P + last_row / G + 1 : P;    // keys this row tile can see
     const int n_tiles_unit = (kv_len + BC - 1) / BC;
-    // a unit too short to be worth cutting is done whole by its regular workgroup
-    if (plan.parts > 1 && n_tiles_unit < MIN_TILES_PER_PART * plan.parts) {
+    // a unit that cannot be cut is done whole by its regular workgroup
+    if (plan.parts > 1 && !cuttable(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1)) {
         if (plan.part > 0) return;
         plan.parts = 1;
     }
-    // this workgroup's key tiles: t_begin .. t_begin + n_tiles - 1.  Every piece of a cut unit starts with a
-    // tile all of whose keys every row sees (the unit has at least 16 tiles per piece and a row tile spans
-    // at most 256 tokens), so the first row maximum is finite in every piece.
+    // this workgroup's key tiles: t_begin .. t_begin + n_tiles - 1
     const int t_begin = plan.part * n_tiles_unit / plan.parts;
     const int n_tiles = (plan.part + 1) * n_tiles_unit / plan.parts - t_begin;
 
@@ -762,7 +770,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int P = b.prefix_lens[r];
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = a.causal ? P + last_row / G + 1 : P;
-    if ((kv_len + BC - 1) / BC < MIN_TILES_PER_PART * plan.parts) return;   // the unit was done whole
+    if (!cuttable((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1)) return;   // done whole
 
     const int tid = threadIdx.x;
     const float c_log2 = b.softmax_scale * 1.44269504088896340736f;

@@ -113,14 +113,17 @@ def test_ragged_cross_sweep():
 
 # Batches whose last work units are cut along the key axis and merged by the second kernel.  A unit is a
 # 256-row tile of one (request, KV head) pair; pairs are dealt to the 8 XCDs; the units an XCD has left over
-# after its full rounds of 32 are cut into 4 pieces (1..8 left over) or 2 (9..12) when they are long enough.
+# after its full rounds of 32 are cut into 4 pieces (1..8 left over) or 2 (9..12) when every piece gets at least
+# 16 key tiles and starts below the diagonal.
 CUT_CASES = [
     # name, kind, H, Hkv, prefix lens, new lens
     ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 2 units per XCD on 4 XCDs, 4 pieces each
     ("cut2_causal", "causal", 28, 4, [2100], [350]),                # 10 units per XCD, 2 pieces each
     ("cut4_cross", "cross", 32, 8, [6404, 6404], [100, 37]),        # 3 units per XCD, 4 pieces; ragged last tile
     ("cut_mixed", "causal", 16, 8, [8000, 100, 4100], [64, 200, 3]),  # long units are cut, short ones are not
-    ("cut_edge", "causal", 8, 8, [4032 - 5, 4096 - 5], [5, 5]),     # 63 and 64 key tiles: just below / at the bar
+    ("cut_edge", "causal", 8, 8, [4091, 4096, 4000, 1800], [5, 5, 200, 300]),  # 64 tiles: just cut; 63: not cut;
+                                                                    # a last piece that would start on the diagonal
+    ("cut_short", "causal", 28, 4, [1056], [300]),                  # 9 units per XCD, too short to cut
     ("cut_gqa1", "causal", 8, 8, [4100], [300]),                    # one head per group: 256 tokens per row tile
 ]
 
