@@ -29,12 +29,20 @@
 // P(i) = exp2(S(i) - m), then O += V(i)^T P(i) (16 MFMA) while the VALU takes the row maximum of
 // S(i+1); the body is written as 32 one-MFMA slices fenced by scheduling barriers, so the issue
 // order is the written one.  The row sums of P (of the bf16-rounded values, so that the normaliser
-// matches the numerator) are taken on the matrix pipe as well, with eight small 4x4x4 MFMAs per tile:
-// dot-product instructions on the VALU do not overlap with MFMAs.  The running maximum m may lag the true maximum by up to 2^8 (it only
-// has to keep exp2 in range); O and l are rescaled only when a row exceeds that.  K and V tiles
-// live in 4-deep rings in LDS, fetched two iterations ahead, with one workgroup barrier per tile
-// placed mid-iteration; the loop body exists in four copies (ring slot) so buffer offsets and
-// register roles are compile-time constants.
+// matches the numerator) are taken on the matrix pipe as well, with eight small 4x4x4 MFMAs per
+// tile: dot-product instructions on the VALU do not overlap with MFMAs.  The running maximum m may
+// lag the true maximum by up to 2^8 (it only has to keep exp2 in range); O and l are rescaled only
+// when a row exceeds that.  K and V tiles live in 4-deep rings in LDS, fetched two iterations ahead,
+// with one workgroup barrier per tile placed mid-iteration; the loop body exists in four copies
+// (ring slot) so buffer offsets and register roles are compile-time constants.
+//
+// Work units left over after an XCD's full rounds of 32 are cut along the key axis and merged by
+// attn_bf16_merge_kernel (see "Work units" below).
+//
+// Cost model (measured on gfx950): per MFMA of 32 cycles the SIMD's VALU issue port is taken ~13 cycles
+// by the MFMA itself, ~4.3 by each plain VALU instruction, ~8.6 by v_exp_f32, and ~5.6 per KiB of LDS
+// data returned; the loop needs fma + exp + 1/2 cvt + 1/2 max per MFMA plus the row sums, i.e. it is
+// bound by that port (about 49 cycles per MFMA), not by the matrix pipe.
 #include "emm_internal.h"
 
 #include <type_traits>
