@@ -155,6 +155,29 @@ def test_few_pairs_spread_over_xcds(H, Hkv, prefix, new):
     print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_batches_sampled(seed):
+    """Random batch shapes (request count, head grouping, prefix and new-token lengths from a few tokens to
+    several thousand, empty requests, both kinds): every launch shape the planner can produce -- whole and
+    cut units, pairs fanned out over XCDs, ragged last tiles -- against the oracle on sampled tokens."""
+    rng = np.random.default_rng(4000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 7]))
+    n_req = int(rng.choice([1, 1, 2, 3, 5, 9, 20]))
+    kind = "cross" if seed % 4 == 3 else "causal"
+    scale = int(rng.choice([40, 400, 3000, 9000]))
+    prefix = [int(x) for x in rng.integers(0, scale + 1, size=n_req)]
+    new = [int(x) for x in rng.integers(0, max(2, scale // int(rng.choice([1, 4, 30]))) + 1, size=n_req)]
+    if sum(new) == 0:
+        new[0] = 17
+    print("case random", seed, kind, "H", Hkv * G, "Hkv", Hkv, "prefix", prefix, "new", new, flush=True)
+    wl = W.build_workload("random%d" % seed, kind, "bf16", 4100 + seed, num_q_heads=Hkv * G, num_kv_heads=Hkv,
+                          head_dim=128, page_size=16, prefix_lens=prefix, new_lens=new)
+    dw = _gpu_run(wl)
+    tokens = None if wl.total_new_tokens <= 96 else _sample_tokens(wl, 64, seed=seed)
+    print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
