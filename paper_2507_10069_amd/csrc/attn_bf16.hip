@@ -538,7 +538,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         // softmax arithmetic fills the VALU slots in between.
         //   slices  0..15  S(i+1) = K(i+1) Q^T        + exp2 work on S(i), key block 0 then 1; tile fetches
         //   slices 16..23  O += V(i)^T P(i), block 0  + rest of the exp2 work (block 1)
-        //   slices 24..31  O += V(i)^T P(i), block 1  + row maximum of S(i+1)
+        //   slices 24..31  O += V(i)^T P(i), block 1  + row sums of P(i) (slice 24), row maximum of S(i+1)
         // Operands are read from LDS PF_DIST slices ahead of their MFMA.
         auto iteration = [&](int i, auto par) {
             constexpr int R = decltype(par)::value;
@@ -668,9 +668,16 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                     if constexpr (k == 8) m2 = fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]);
                     else m2 = fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), mx);
                     mx = fmaxf(fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]), m2);
-                    // row sum of P(i), four values per slice, on the matrix pipe
-                    constexpr int u = k - 8;
-                    psum = sum4_bf16(pw[u >> 2][(u >> 1) & 1][2 * (u & 1)], pw[u >> 2][(u >> 1) & 1][2 * (u & 1) + 1], psum);
+                }
+                if constexpr (k == 8) {
+                    // row sums of P(i) on the matrix pipe, all eight back to back: switching between MFMA
+                    // shapes costs the pipe about 16 cycles each time (measured), so they are not spread out
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<0, 8>([&](auto uc) {
+                        constexpr int u = decltype(uc)::value;
+                        psum = sum4_bf16(pw[u >> 2][(u >> 1) & 1][2 * (u & 1)], pw[u >> 2][(u >> 1) & 1][2 * (u & 1) + 1], psum);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });
