@@ -6,13 +6,14 @@
  * plus shared text) already have their key/value entries in a paged KV pool (Appendix A), and
  * prefill runs only over the remaining "new" tokens, reading the cached entries instead of
  * recomputing them.  Appendix B.7 states what the result must be: identical to prefilling the
- * whole sequence.  Three device operations are exported:
+ * whole sequence.  These device operations are exported:
  *
  *   emm_kv_scatter    store the new tokens' K/V rows in their pool slots          (Section 2.2)
  *   emm_prefill_attn  causal grouped-query attention of the new tokens over
  *                     cached prefix + new tokens, read from the pool       (Section 3.3, App. B.7)
  *   emm_cross_attn    unmasked attention of text queries over cached image K/V
  *                     for encoder-decoder models                                  (Section 2.1)
+ *   emm_decode_attn   the same attention for the decode step, one new token per request (Section 2.2)
  *
  * Conventions common to all calls
  *   - Every pointer marked "device" is memory of the current HIP device, owned by the caller; the
@@ -86,8 +87,8 @@ typedef struct {
 emm_status emm_kv_scatter(const emm_batch *batch, const void *k_new, const void *v_new,
                           void *k_cache, void *v_cache, void *hip_stream);
 
-/* Bytes of device workspace emm_prefill_attn / emm_cross_attn need for this batch (0 for EMM_F32, about
- * 134 MB for EMM_BF16 whatever the batch).  The bf16 kernels cut the work units left over after an
+/* Bytes of device workspace emm_prefill_attn / emm_cross_attn need for this batch (0 for EMM_F32; for EMM_BF16 about
+ * 134 MB, or for a decode batch 8 KB per (request, KV head, 512..3584 keys of the longest possible context)).  The bf16 kernels cut the work units left over after an
  * XCD's full rounds of 32 along the key axis, park the pieces' accumulators there and merge them with
  * a second kernel on the same stream; the contents need no initialisation and mean nothing afterwards.
  * Calls on different streams must not share a workspace.  Host-only; reads only the scalar fields. */
@@ -109,6 +110,19 @@ emm_status emm_prefill_attn_workspace_size(const emm_batch *batch, size_t *bytes
 emm_status emm_prefill_attn(const emm_batch *batch, const void *q, const void *k_cache,
                             const void *v_cache, void *out, float *lse, void *workspace,
                             size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Decode-step attention (Section 2.2: after prefill the decode stage produces one token per iteration
+ * from the cached K/V of all earlier tokens, and is memory bound).  emm_prefill_attn for a batch in which
+ * every request has at most one new token (max_new_len <= 1, else EMM_ERR_INVALID_ARG): the token of
+ * request r attends to slots 0 .. prefix_lens[r], its own K/V having been scattered first.  Arguments,
+ * workspace and results as for emm_prefill_attn, which takes the same path for such a batch by itself;
+ * the bf16 kernel behind it reads every K/V byte once, cutting each request's context into pieces that
+ * fill the chip and merging them through the workspace.
+ */
+emm_status emm_decode_attn(const emm_batch *batch, const void *q, const void *k_cache,
+                           const void *v_cache, void *out, float *lse, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
 
 /*
  * Cross-attention variant (Section 2.1: in encoder-decoder MLLMs text tokens meet vision tokens

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libemm.so")
 EMM_OK, EMM_ERR_NULL, EMM_ERR_INVALID_ARG, EMM_ERR_UNSUPPORTED, EMM_ERR_WORKSPACE, EMM_ERR_LAUNCH = range(6)
 EMM_F32, EMM_BF16 = 0, 1
 
-EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn",
+EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
            "emm_validate_batch_host", "emm_status_string", "emm_version"]
 
 
@@ -59,7 +59,7 @@ def load() -> ctypes.CDLL:
     lib.emm_kv_scatter.argtypes = [bp, vp, vp, vp, vp, vp]
     lib.emm_prefill_attn_workspace_size.restype = ctypes.c_int
     lib.emm_prefill_attn_workspace_size.argtypes = [bp, ctypes.POINTER(ctypes.c_size_t)]
-    for name in ("emm_prefill_attn", "emm_cross_attn"):
+    for name in ("emm_prefill_attn", "emm_cross_attn", "emm_decode_attn"):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -134,6 +134,10 @@ def emm_prefill_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, works
 
 def emm_cross_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, workspace=None, stream=None) -> None:
     _attn("emm_cross_attn", batch, q, k_cache, v_cache, out, lse, workspace, stream)
+
+
+def emm_decode_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, workspace=None, stream=None) -> None:
+    _attn("emm_decode_attn", batch, q, k_cache, v_cache, out, lse, workspace, stream)
 
 
 def emm_validate_batch_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray,

@@ -96,8 +96,10 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     args.causal = causal;
     args.workspace = need > 0 ? workspace : nullptr;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const hipError_t err = (b->dtype == EMM_BF16) ? emm::launch_attn_bf16_d128(args, stream)
-                                                  : emm::launch_attn_f32(args, stream);
+    hipError_t err;
+    if (b->dtype != EMM_BF16) err = emm::launch_attn_f32(args, stream);
+    else if (emm::attn_bf16_decode_applies(args.b)) err = emm::launch_attn_bf16_decode(args, stream);
+    else err = emm::launch_attn_bf16_d128(args, stream);
     return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
 }
 
@@ -133,13 +135,24 @@ emm_status emm_prefill_attn_workspace_size(const emm_batch* b, size_t* bytes)
     if (st != EMM_OK) return st;
     st = check_supported(b);
     if (st != EMM_OK) return st;
-    if (b->dtype == EMM_BF16) *bytes = emm::attn_bf16_d128_workspace_bytes();
+    if (b->dtype == EMM_BF16) {
+        const emm::BatchView v = view_of(b);
+        *bytes = emm::attn_bf16_decode_applies(v) ? emm::attn_bf16_decode_workspace_bytes(v)
+                                                  : emm::attn_bf16_d128_workspace_bytes();
+    }
     return EMM_OK;
 }
 
 emm_status emm_prefill_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,
                             void* out, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1);
+}
+
+emm_status emm_decode_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,
+                           void* out, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
     return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1);
 }
 

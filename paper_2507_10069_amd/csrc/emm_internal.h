@@ -35,5 +35,9 @@ hipError_t launch_kv_scatter(const BatchView& b, const void* k_new, const void* 
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream);
 size_t attn_bf16_d128_workspace_bytes();   // what launch_attn_bf16_d128 wants behind AttnArgs::workspace
+// decode step (every request has at most one query token, at most 16 query heads per KV head)
+bool attn_bf16_decode_applies(const BatchView& b);
+size_t attn_bf16_decode_workspace_bytes(const BatchView& b);
+hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace emm

@@ -57,6 +57,17 @@ def test_workspace_size_and_scalar_checks():
             B.EMM_ERR_UNSUPPORTED, over
 
 
+def test_decode_entry_wants_at_most_one_new_token():
+    lib = B.load()
+    ok = 0x1000
+    b = _batch()                     # max_new_len = 12
+    b.page_table = b.prefix_lens = b.new_lens = b.cu_new_lens = ok
+    assert lib.emm_decode_attn(ctypes.byref(b), ok, ok, ok, ok, None, ok, 1 << 30, None) == B.EMM_ERR_INVALID_ARG
+    one = _batch(total_new_tokens=2, max_new_len=1)
+    assert B.emm_prefill_attn_workspace_size(one) > 0
+    assert lib.emm_decode_attn(ctypes.byref(one), ok, ok, ok, ok, None, None, 0, None) == B.EMM_ERR_NULL
+
+
 @pytest.mark.parametrize("entry", ["emm_prefill_attn", "emm_cross_attn"])
 def test_attention_rejects_before_launch(entry):
     lib = B.load()

@@ -178,6 +178,35 @@ def test_random_batches_sampled(seed):
     print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
 
 
+DECODE_CASES = [
+    # name, kind, H, Hkv, context lengths before the new token, new lens (0 = request without a query token)
+    ("decode_mixed", "causal", 28, 4, [0, 1, 15, 16, 62, 63, 64, 65, 127, 128, 500, 1056, 4095, 4096, 9000], [1] * 15),
+    ("decode_long", "causal", 32, 8, [20000, 18431, 3, 7000], [1, 1, 1, 1]),        # several pieces per request
+    ("decode_holes", "causal", 8, 8, [300, 40, 0, 2000, 77], [1, 0, 1, 1, 0]),      # G = 1; requests without a token
+    ("decode_g16", "causal", 16, 1, [1500, 64], [1, 1]),                             # 16 heads on one KV head
+    ("decode_g17", "causal", 34, 2, [700, 129], [1, 1]),                             # too wide: the prefill kernel does it
+    ("decode_cross", "cross", 32, 8, [6404, 0, 17, 1601], [1, 1, 1, 1]),             # one text query over image K/V
+    ("decode_single", "causal", 28, 4, [16384], [1]),                                # one request, long context
+]
+
+
+@pytest.mark.parametrize("name,kind,H,Hkv,ctx,new", DECODE_CASES)
+def test_decode_step_parity(name, kind, H, Hkv, ctx, new):
+    """The decode step (at most one new token per request) through emm_decode_attn and, for the same batch,
+    through emm_prefill_attn, against the oracle; the two entry points must agree bit for bit."""
+    print("case", name, flush=True)
+    wl = W.build_workload(name, kind, "bf16", 1200 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=ctx, new_lens=new)
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+    if kind == "causal":
+        first = B.DeviceWorkload.to_numpy_bits(dw.out).tobytes()
+        dw.out.zero_()
+        B.emm_decode_attn(dw.batch, dw.q, dw.k_cache, dw.v_cache, dw.out, dw.lse, dw.workspace)
+        torch.cuda.synchronize()
+        assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
