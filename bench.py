@@ -95,6 +95,9 @@ def main():
                     help="also run a plain 256 MiB device copy 5 times (a kernel of known HBM traffic, used to "
                          "scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--others", action="store_true", help="also time the other named workloads (stderr + JSON)")
+    ap.add_argument("--decode", default=None, metavar="NAME",
+                    help="time one decode-step workload instead (one query token per request; HBM-bound): "
+                         "decode_video_b8, decode_mixed_b32 or decode_b64_8k")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between requests); "
@@ -116,6 +119,26 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.decode is not None:
+        wl = W.decode_config(args.decode)
+        dw = B.DeviceWorkload(wl)
+        ms, attn_ms, scat_ms = time_workload(dw, args.steps, args.warmup)
+        gbs = wl.kv_read_bytes() / (attn_ms * 1e-3) / 1e9
+        log("workload %s: %.4f ms/step (attention %.4f ms, scatter %.4f ms), %.0f GB/s of K/V read"
+            % (wl.name, ms, attn_ms, scat_ms, gbs))
+        print(json.dumps({
+            "metric": "decode_attention_kv_read_gbs", "value": wl.kv_read_bytes() / (ms * 1e-3) / 1e9, "unit": "GB/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+            "config": {"workload": wl.name, "requests": wl.num_reqs, "kv_read_bytes_per_step": wl.kv_read_bytes(),
+                       "parallelism": "single-gpu"},
+            "new_tokens_per_s": wl.total_new_tokens / (ms * 1e-3), "attention_ms": attn_ms, "scatter_ms": scat_ms,
+            "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                         "kernel": "attn_bf16_decode_kernel + attn_bf16_decode_merge_kernel"},
+        }), flush=True)
+        return
 
     wl = W.config(args.workload)
     dw = B.DeviceWorkload(wl)
@@ -155,6 +178,16 @@ def main():
                               "tflops": w.attention_flops() / (m * 1e-3) / 1e12,
                               "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
             log("workload %s: %s" % (w.name, others[w.name]))
+            del d
+        for name in W.DECODE_CONFIGS:
+            w = W.decode_config(name)
+            d = B.DeviceWorkload(w)
+            m, am, sm = time_workload(d, 30, 5)
+            others[name] = {"ms_per_step": m, "attention_ms": am, "scatter_ms": sm,
+                            "kv_read_gbs": w.kv_read_bytes() / (am * 1e-3) / 1e9,
+                            "frac_hbm_peak": w.kv_read_bytes() / (am * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
+            log("workload %s: %s" % (name, others[name]))
             del d
         result["other_workloads"] = others
     if not args.no_cpu_baseline:

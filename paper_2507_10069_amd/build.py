@@ -46,7 +46,7 @@ def build_microbenchmark(verbose: bool = False) -> list:
     """Compiles the stand-alone microbenchmarks (executables; the library does not use them)."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     exes = []
-    for name in ("mfma_lds_rates", "valu_issue_costs"):
+    for name in ("mfma_lds_rates", "valu_issue_costs", "hbm_read_rates"):
         exe = os.path.join(OBJ_DIR, name)
         cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-o", exe, os.path.join(CSRC, name + ".hip")]

@@ -95,6 +95,15 @@ class Workload:
         """Algorithmic FLOPs: 2*d for each score and 2*d for each weighted-V row, unmasked pairs only."""
         return 4 * self.head_dim * self.num_q_heads * self.attended_pairs()
 
+    def kv_read_bytes(self) -> int:
+        """Bytes of K and V a step must read at least once: every slot the queries of a request can see,
+        all KV heads (what bounds the decode step, where nothing is reused)."""
+        total = 0
+        for p, n in zip(self.prefix_lens.tolist(), self.new_lens.tolist()):
+            if n > 0:
+                total += p + (n if self.kind == "causal" else 0)
+        return 2 * total * self.num_kv_heads * self.head_dim * self.elt_bytes
+
     def scatter_bytes(self) -> int:
         """Bytes the KV scatter must move: read K,V of the new tokens and write them once."""
         if self.kind != "causal":
@@ -292,6 +301,26 @@ def config5(shrink: int = 1) -> Workload:
     return wl
 
 
+def decode_config(name: str, shrink: int = 1) -> Workload:
+    """Decode-step batches (one new token per request, the stage after prefill): the contexts that the
+    prefill workloads leave behind.
+      decode_video_b8   8 requests with the video context of config 3 (16384 + 2048 tokens), 28/4 heads
+      decode_mixed_b32  the 32 requests of config 4 after their prefill (context = prefix + new), 32/8 heads
+      decode_b64_8k     64 requests of 8192 tokens, 28/4 heads"""
+    if name == "decode_video_b8":
+        ctx, H, Hkv, seed = [_s(16384 + 2048, shrink)] * 8, 28, 4, 2001
+    elif name == "decode_mixed_b32":
+        c4 = config4(shrink)
+        ctx, H, Hkv, seed = [int(p) + int(n) for p, n in zip(c4.prefix_lens, c4.new_lens)], 32, 8, 2002
+    elif name == "decode_b64_8k":
+        ctx, H, Hkv, seed = [_s(8192, shrink)] * 64, 28, 4, 2003
+    else:
+        raise KeyError(name)
+    return build_workload(name, "causal", "bf16", seed, num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=ctx, new_lens=[1] * len(ctx), spare_pages=8)
+
+
+DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k")
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
