@@ -50,7 +50,9 @@ typedef enum {
     EMM_ERR_INVALID_ARG = 2,   /* a scalar field is out of range or a pointer is misaligned    */
     EMM_ERR_UNSUPPORTED = 3,   /* valid request, but no kernel for this dtype/head_dim/page    */
     EMM_ERR_WORKSPACE = 4,     /* workspace_bytes smaller than emm_prefill_attn_workspace_size */
-    EMM_ERR_LAUNCH = 5         /* the HIP runtime refused the launch                           */
+    EMM_ERR_LAUNCH = 5,        /* the HIP runtime refused the launch                           */
+    EMM_ERR_NO_SPACE = 6,      /* prefix cache: every page is held by a live request           */
+    EMM_ERR_NOT_FOUND = 7      /* prefix cache: no live request with this id                   */
 } emm_status;
 
 typedef enum { EMM_F32 = 0, EMM_BF16 = 1 } emm_dtype;

@@ -215,6 +215,8 @@ const char* emm_status_string(emm_status s)
         case EMM_ERR_UNSUPPORTED: return "unsupported dtype / head_dim / page_size";
         case EMM_ERR_WORKSPACE: return "workspace too small";
         case EMM_ERR_LAUNCH: return "HIP launch failed";
+        case EMM_ERR_NO_SPACE: return "no free or evictable page left";
+        case EMM_ERR_NOT_FOUND: return "unknown request id";
     }
     return "unknown status";
 }
