@@ -83,6 +83,80 @@ def read_traffic():
         return None
 
 
+def bench_prefix_cache(with_model: bool):
+    """Host-side prefix cache on a stream shaped like the paper's multimodal traffic: a few system prompts,
+    a catalogue of images (576..4096 vision tokens) and videos (16384), a private question per request, four
+    requests alive at a time, a pool that holds about 1 M tokens so that eviction is constant.  Times
+    begin (match + allocate), commit (publish) and release through the C ABI; the reference model is timed on
+    a bounded sample of the same stream."""
+    import numpy as np
+    from paper_2507_10069_amd import prefix_cache as PC
+
+    rng = np.random.default_rng(31)
+    ps, num_pages, max_pages = 16, 65536, 2048
+    prompts = [rng.integers(0, 150000, int(n)) for n in (40, 120, 300)]
+    images = [PC.emm_mm_token_ids(PC.emm_mm_content_hash(b"image-%d" % i), int(rng.integers(576, 4097))) for i in range(300)]
+    videos = [PC.emm_mm_token_ids(PC.emm_mm_content_hash(b"video-%d" % i), 16384) for i in range(24)]
+
+    def stream(n):
+        out = []
+        for _ in range(n):
+            item = videos[rng.integers(len(videos))] if rng.random() < 0.15 else images[rng.integers(len(images))]
+            out.append(np.concatenate([prompts[rng.integers(3)], item, rng.integers(0, 150000, int(rng.integers(16, 257)))]))
+        return out
+
+    def drive(begin, commit, release, reqs):
+        t = {"begin": 0.0, "commit": 0.0, "release": 0.0}
+        live = []
+        for tok in reqs:
+            t0 = time.perf_counter()
+            rid = begin(tok)
+            t1 = time.perf_counter()
+            commit(rid, len(tok))
+            t2 = time.perf_counter()
+            t["begin"] += t1 - t0
+            t["commit"] += t2 - t1
+            live.append(rid)
+            if len(live) > 4:
+                t0 = time.perf_counter()
+                release(live.pop(0))
+                t["release"] += time.perf_counter() - t0
+        for rid in live:
+            release(rid)
+        return t
+
+    reqs = stream(4000)
+    tokens = int(sum(len(r) for r in reqs))
+    cache = PC.emm_prefix_cache_create(num_pages, ps)
+    t = drive(lambda tok: PC.emm_prefix_cache_begin(cache, tok, max_pages)[2],
+              lambda rid, n: PC.emm_prefix_cache_commit(cache, rid, n),
+              lambda rid: PC.emm_prefix_cache_release(cache, rid), reqs)
+    st = PC.emm_prefix_cache_get_stats(cache)
+    PC.emm_prefix_cache_destroy(cache)
+    total = sum(t.values())
+    result = {
+        "metric": "prefix_cache_tokens_per_s", "value": tokens / total, "unit": "tokens/s", "n_gpus": 0,
+        "steps": len(reqs), "warmup": 0, "ms_per_step": 1e3 * total / len(reqs), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+        "config": {"workload": "4000 requests: system prompt + image (576..4096 tokens) or video (16384) + question, "
+                               "page 16, pool 65536 pages, 5 live requests", "tokens": tokens},
+        "us_per_request": {k: 1e6 * v / len(reqs) for k, v in t.items()},
+        "requests_per_s": len(reqs) / total, "hit_rate": st["hit_tokens"] / st["lookup_tokens"],
+        "evictions": st["evictions"],
+    }
+    if with_model:
+        from oracle import prefix_cache_model as M
+        sample = reqs[:150]
+        model = M.PrefixCacheModel(num_pages, ps)
+        tm = drive(lambda tok: model.begin(tok.tolist(), max_pages)[2], lambda rid, n: model.commit(rid, n),
+                   lambda rid: model.release(rid), sample)
+        result["cpu_baseline"] = {"value": sum(len(r) for r in sample) / sum(tm.values()), "unit": "tokens/s", "cores": 1,
+                                  "kind": "oracle", "sample": "first 150 requests of the stream on the reference model"}
+    log("prefix cache: %.0f requests/s, %.1f M tokens/s, hit rate %.3f, %d evictions; us per request %s"
+        % (result["requests_per_s"], result["value"] / 1e6, result["hit_rate"], st["evictions"], result["us_per_request"]))
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,7 +172,11 @@ def main():
     ap.add_argument("--decode", default=None, metavar="NAME",
                     help="time one decode-step workload instead (one query token per request; HBM-bound): "
                          "decode_video_b8, decode_mixed_b32 or decode_b64_8k")
+    ap.add_argument("--prefix-cache", action="store_true",
+                    help="time the host-side prefix cache (no GPU work) on a synthetic request stream")
     args = ap.parse_args()
+    if args.prefix_cache:
+        return bench_prefix_cache(not args.no_cpu_baseline)
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between requests); "
                  "run with --gpus 1")

@@ -1,5 +1,8 @@
 """fp64 CPU oracle for prefix-cached paged prefill attention.  TEST INFRASTRUCTURE ONLY.
 
+(``prefix_cache_model.py`` beside this file is the reference model of the host-side prefix cache; it is
+plain Python and is imported on its own.)
+
 Importable from ``tests/``, the smoke check and the benchmark's ``cpu_baseline`` leg; nothing in
 the product package imports it, and it imports nothing from the product package.
 

@@ -10,16 +10,19 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libemm.so")
-SOURCES = ["api.hip", "kv_scatter.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_decode.hip"]
+SOURCES = ["api.hip", "kv_scatter.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_decode.hip", "prefix_cache.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instruction forms are switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# host-only translation units (no device code in them)
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-I", os.path.join(os.path.dirname(HERE), "include")]
 
 
 def _compile(src: str, extra) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
+    flags = HOST_FLAGS if src.endswith(".cpp") else FLAGS + list(extra)
+    cmd = [HIPCC] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     lines = [ln for ln in res.stderr.splitlines()
              if "packed-fp32-ops" not in ln and "is not a recognized feature" not in ln]

@@ -28,6 +28,13 @@ def test_exports_match_header():
     assert declared == sorted(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
+    from paper_2507_10069_amd import prefix_cache as PC
+    with open(os.path.join(ROOT, "include", "emm_prefix_cache.h")) as f:
+        header = f.read()
+    declared = sorted(set(re.findall(r"\b(emm_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(PC.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
     assert B.emm_version() >= 100
     assert B.emm_status_string(B.EMM_OK) == "ok"
     assert "workspace" in B.emm_status_string(B.EMM_ERR_WORKSPACE)
