@@ -14,6 +14,7 @@
  *   emm_cross_attn    unmasked attention of text queries over cached image K/V
  *                     for encoder-decoder models                                  (Section 2.1)
  *   emm_decode_attn   the same attention for the decode step, one new token per request (Section 2.2)
+ *   emm_decode_attn_shared  the decode step reading pages that several requests share once (Section 3.3)
  *
  * Conventions common to all calls
  *   - Every pointer marked "device" is memory of the current HIP device, owned by the caller; the
@@ -128,6 +129,68 @@ emm_status emm_prefill_attn(const emm_batch *batch, const void *q, const void *k
 emm_status emm_decode_attn(const emm_batch *batch, const void *q, const void *k_cache,
                            const void *v_cache, void *out, float *lse, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Decode step with shared prefixes (Section 3.3: requests repeat system prompts and images, so in a decode
+ * batch several requests hold the SAME physical pages at the head of their page tables; Section 2.2: the
+ * step is bound by reading K/V).  A unit is a run of consecutive requests of the batch together with the
+ * number of leading tokens they share; the shared keys and values are then read once per unit instead of
+ * once per request, the result is the same attention as emm_decode_attn up to rounding order.
+ * Contract for unit u = (first, n, shared_len), all arrays device memory:
+ *   - requests first .. first+n-1 each have exactly one new token, n >= 2 and n * (num_q_heads /
+ *     num_kv_heads) <= 32;
+ *   - shared_len is a multiple of 32, >= 32 and <= prefix_lens[r] of every member, and the members' page
+ *     tables agree on entries 0 .. shared_len/page_size - 1;
+ *   - req_unit[r] is the unit of request r or -1, req_shared_len[r] the shared_len of that unit or 0; units
+ *     do not overlap.
+ * emm_shared_prefix_plan_host derives such units from host copies of the batch arrays.
+ */
+typedef struct {
+    int32_t num_units;                 /* U >= 0; with 0 the call is emm_decode_attn with a planning hint    */
+    int32_t planned_tiles;             /* hint, host value: sum over units of shared_len / 32 plus sum over  */
+                                       /* requests of ceil((tokens the query sees - req_shared_len) / 32);   */
+                                       /* 0 = unknown.  Only the way work is cut depends on it, never the    */
+                                       /* result: without it every context is planned as the longest one the  */
+                                       /* page table can hold, which under-fills the chip on ragged batches.  */
+    int32_t max_own_tiles;             /* bound, host value: the largest ceil((tokens the query sees -        */
+                                       /* req_shared_len) / 32) over the requests; 0 = not given (the page     */
+                                       /* table's width is used).  Unlike the hint it MUST hold when given:    */
+                                       /* the grid provides pieces for own parts up to this length only.      */
+    int32_t max_unit_tiles;            /* bound, host value: the largest shared_len / 32; 0 = not given        */
+    const int32_t *unit_first_req;     /* device [U]                                                         */
+    const int32_t *unit_num_reqs;      /* device [U]                                                         */
+    const int32_t *unit_shared_len;    /* device [U]                                                         */
+    const int32_t *req_unit;           /* device [B]                                                         */
+    const int32_t *req_shared_len;     /* device [B]                                                         */
+} emm_shared_prefix;
+
+/* Workspace bytes of emm_decode_attn_shared for this batch and the four scalar fields of `shared` (the values
+ * the call itself will be given; num_units <= num_reqs / 2; the pointers are not looked at).
+ * EMM_ERR_UNSUPPORTED unless the batch is EMM_BF16, head_dim 128, at most 16 query heads per KV head. */
+emm_status emm_decode_attn_shared_workspace_size(const emm_batch *batch, const emm_shared_prefix *shared,
+                                                 size_t *bytes);
+
+/* Arguments as for emm_decode_attn, plus the units (`shared` itself is host memory, its arrays device). */
+emm_status emm_decode_attn_shared(const emm_batch *batch, const emm_shared_prefix *shared, const void *q,
+                                  const void *k_cache, const void *v_cache, void *out, float *lse,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Finds units in a batch given as HOST copies of its arrays: greedily, from each request on, the following
+ * requests are added while their page tables share a prefix with the first one's of at least
+ * max(32, min_shared_tokens) tokens (whole pages that both requests' cached tokens fill, rounded down to a
+ * multiple of 32), the rows still fit, and the number of keys saved, shared_len * (n - 1), does not go down.
+ * Requests that share pages must therefore be adjacent in the batch to be found.  Outputs are host arrays:
+ * unit_* of length >= num_reqs / 2, req_* of length num_reqs; the four scalar fields of *shared are filled in
+ * (its pointers are left alone: set them to the device copies of the arrays).  The hint and the bounds are
+ * useful even with no units at all when the contexts are very unequal or much shorter than the page table
+ * is wide.  Only the scalar fields of `batch` are read.
+ */
+emm_status emm_shared_prefix_plan_host(const emm_batch *batch, const int32_t *host_page_table,
+                                       const int32_t *host_prefix_lens, const int32_t *host_new_lens,
+                                       int32_t min_shared_tokens, int32_t *unit_first_req,
+                                       int32_t *unit_num_reqs, int32_t *unit_shared_len, int32_t *req_unit,
+                                       int32_t *req_shared_len, emm_shared_prefix *shared);
 
 /*
  * Cross-attention variant (Section 2.1: in encoder-decoder MLLMs text tokens meet vision tokens

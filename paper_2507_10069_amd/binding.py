@@ -20,6 +20,7 @@ EMM_OK, EMM_ERR_NULL, EMM_ERR_INVALID_ARG, EMM_ERR_UNSUPPORTED, EMM_ERR_WORKSPAC
 EMM_F32, EMM_BF16 = 0, 1
 
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
+           "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
            "emm_validate_batch_host", "emm_status_string", "emm_version"]
 
 
@@ -36,6 +37,13 @@ class emm_batch(ctypes.Structure):
                 ("max_new_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("reserved", ctypes.c_int32), ("page_table", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
                 ("new_lens", ctypes.c_void_p), ("cu_new_lens", ctypes.c_void_p)]
+
+
+class emm_shared_prefix(ctypes.Structure):
+    _fields_ = [("num_units", ctypes.c_int32), ("planned_tiles", ctypes.c_int32),
+                ("max_own_tiles", ctypes.c_int32), ("max_unit_tiles", ctypes.c_int32), ("unit_first_req", ctypes.c_void_p),
+                ("unit_num_reqs", ctypes.c_void_p), ("unit_shared_len", ctypes.c_void_p), ("req_unit", ctypes.c_void_p),
+                ("req_shared_len", ctypes.c_void_p)]
 
 
 _lib = None
@@ -63,6 +71,12 @@ def load() -> ctypes.CDLL:
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.emm_decode_attn_shared_workspace_size.restype = ctypes.c_int
+    lib.emm_decode_attn_shared_workspace_size.argtypes = [bp, ctypes.POINTER(emm_shared_prefix), ctypes.POINTER(ctypes.c_size_t)]
+    lib.emm_decode_attn_shared.restype = ctypes.c_int
+    lib.emm_decode_attn_shared.argtypes = [bp, ctypes.POINTER(emm_shared_prefix), vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.emm_shared_prefix_plan_host.restype = ctypes.c_int
+    lib.emm_shared_prefix_plan_host.argtypes = [bp, i32p, i32p, i32p, ctypes.c_int32] + [i32p] * 5 + [ctypes.POINTER(emm_shared_prefix)]
     lib.emm_validate_batch_host.restype = ctypes.c_int
     lib.emm_validate_batch_host.argtypes = [bp, i32p, i32p, i32p, i32p, ctypes.c_int]
     lib.emm_status_string.restype = ctypes.c_char_p
@@ -140,6 +154,47 @@ def emm_decode_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, worksp
     _attn("emm_decode_attn", batch, q, k_cache, v_cache, out, lse, workspace, stream)
 
 
+def emm_decode_attn_shared_workspace_size(batch: emm_batch, shared: emm_shared_prefix) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().emm_decode_attn_shared_workspace_size(ctypes.byref(batch), ctypes.byref(shared), ctypes.byref(n)),
+           "emm_decode_attn_shared_workspace_size")
+    return int(n.value)
+
+
+def make_shared_prefix(num_units: int, unit_first_req=None, unit_num_reqs=None, unit_shared_len=None, req_unit=None,
+                       req_shared_len=None, planned_tiles: int = 0, max_own_tiles: int = 0,
+                       max_unit_tiles: int = 0) -> emm_shared_prefix:
+    """Fill the descriptor; the five arrays are int32 device tensors."""
+    return emm_shared_prefix(num_units, planned_tiles, max_own_tiles, max_unit_tiles, _ptr(unit_first_req), _ptr(unit_num_reqs), _ptr(unit_shared_len),
+                             _ptr(req_unit), _ptr(req_shared_len))
+
+
+def emm_decode_attn_shared(batch: emm_batch, shared: emm_shared_prefix, q, k_cache, v_cache, out, lse=None,
+                           workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    _check(load().emm_decode_attn_shared(ctypes.byref(batch), ctypes.byref(shared), _ptr(q), _ptr(k_cache),
+                                         _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
+                                         _stream(stream)), "emm_decode_attn_shared")
+
+
+def emm_shared_prefix_plan_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray,
+                                new_lens: np.ndarray, min_shared_tokens: int = 32) -> dict:
+    """Returns the units as host int32 arrays: unit_first_req, unit_num_reqs, unit_shared_len (length U),
+    req_unit, req_shared_len (length B), and the four scalars of the descriptor."""
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    ins = [np.ascontiguousarray(a, dtype=np.int32) for a in (page_table, prefix_lens, new_lens)]
+    B_ = int(batch.num_reqs)
+    outs = [np.zeros(max(B_ // 2, 1), dtype=np.int32) for _ in range(3)] + [np.zeros(max(B_, 1), dtype=np.int32) for _ in range(2)]
+    sp = emm_shared_prefix()
+    _check(load().emm_shared_prefix_plan_host(ctypes.byref(batch), *[a.ctypes.data_as(i32p) for a in ins],
+                                              min_shared_tokens, *[a.ctypes.data_as(i32p) for a in outs],
+                                              ctypes.byref(sp)), "emm_shared_prefix_plan_host")
+    U = int(sp.num_units)
+    return {"num_units": U, "planned_tiles": int(sp.planned_tiles), "max_own_tiles": int(sp.max_own_tiles),
+            "max_unit_tiles": int(sp.max_unit_tiles), "unit_first_req": outs[0][:U], "unit_num_reqs": outs[1][:U], "unit_shared_len": outs[2][:U],
+            "req_unit": outs[3][:B_], "req_shared_len": outs[4][:B_]}
+
+
 def emm_validate_batch_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray,
                             new_lens: np.ndarray, cu_new_lens: np.ndarray, causal: bool) -> int:
     """Returns the status instead of raising: it is a checker."""
@@ -194,6 +249,24 @@ class DeviceWorkload:
     def attention(self, stream=None) -> None:
         fn = emm_prefill_attn if self.wl.kind == "causal" else emm_cross_attn
         fn(self.batch, self.q, self.k_cache, self.v_cache, self.out, self.lse, self.workspace, stream)
+
+    def plan_shared(self, min_shared_tokens: int = 32, use_hint: bool = True) -> dict:
+        """Find the shared-prefix units of a decode batch (host) and move them to the device."""
+        import torch
+        wl = self.wl
+        plan = emm_shared_prefix_plan_host(self.batch, wl.page_table, wl.prefix_lens, wl.new_lens, min_shared_tokens)
+        self.shared_arrays = {k: torch.from_numpy(np.ascontiguousarray(v if len(v) else np.zeros(1, np.int32))).to(self.device)
+                              for k, v in plan.items() if isinstance(v, np.ndarray)}
+        scalars = {k: plan[k] for k in ("planned_tiles", "max_own_tiles", "max_unit_tiles")} if use_hint else {}
+        self.shared = make_shared_prefix(plan["num_units"], **scalars, **self.shared_arrays)
+        ws = emm_decode_attn_shared_workspace_size(self.batch, self.shared)
+        self.shared_workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=self.device)
+        self.shared_plan = plan
+        return plan
+
+    def attention_shared(self, stream=None) -> None:
+        emm_decode_attn_shared(self.batch, self.shared, self.q, self.k_cache, self.v_cache, self.out, self.lse,
+                               self.shared_workspace, stream)
 
     def step(self, stream=None) -> None:
         """One pass of the hot path: scatter the new K/V, then attention."""

@@ -4,7 +4,9 @@
 #include "../../include/emm.h"
 #include "emm_internal.h"
 
+#include <algorithm>
 #include <cmath>
+#include <cstdint>
 #include <vector>
 
 namespace {
@@ -64,16 +66,32 @@ emm::BatchView view_of(const emm_batch* b)
     return v;
 }
 
+emm::SharedPrefixView shared_view_of(const emm_shared_prefix* sp)
+{
+    return emm::SharedPrefixView{sp->unit_first_req, sp->unit_num_reqs, sp->unit_shared_len, sp->req_unit,
+                                 sp->req_shared_len, sp->num_units, sp->planned_tiles, sp->max_own_tiles,
+                                 sp->max_unit_tiles};
+}
+
+// sp: shared-prefix units of a decode batch, or nullptr
 emm_status attention(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache, void* out,
-                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, int causal)
+                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, int causal,
+                     const emm_shared_prefix* sp = nullptr)
 {
     emm_status st = check_scalars(b);
     if (st != EMM_OK) return st;
     st = check_supported(b);
     if (st != EMM_OK) return st;
+    if (sp != nullptr) {
+        if (sp->num_units == 0 && sp->planned_tiles == 0 && sp->max_own_tiles == 0) sp = nullptr;
+    }
     size_t need = 0;
-    st = emm_prefill_attn_workspace_size(b, &need);
+    st = sp != nullptr ? emm_decode_attn_shared_workspace_size(b, sp, &need)
+                       : emm_prefill_attn_workspace_size(b, &need);
     if (st != EMM_OK) return st;
+    if (sp != nullptr && sp->num_units > 0 && (sp->unit_first_req == nullptr || sp->unit_num_reqs == nullptr || sp->unit_shared_len == nullptr ||
+                          sp->req_unit == nullptr || sp->req_shared_len == nullptr))
+        return EMM_ERR_NULL;
     if (b->num_reqs == 0 || b->total_new_tokens == 0) return EMM_OK;
     st = check_arrays(b);
     if (st != EMM_OK) return st;
@@ -97,7 +115,10 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     args.workspace = need > 0 ? workspace : nullptr;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err;
-    if (b->dtype != EMM_BF16) err = emm::launch_attn_f32(args, stream);
+    if (sp != nullptr) {
+        const emm::SharedPrefixView sv = shared_view_of(sp);
+        err = emm::launch_attn_bf16_decode_shared(args, sv, stream);
+    } else if (b->dtype != EMM_BF16) err = emm::launch_attn_f32(args, stream);
     else if (emm::attn_bf16_decode_applies(args.b)) err = emm::launch_attn_bf16_decode(args, stream);
     else err = emm::launch_attn_bf16_d128(args, stream);
     return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
@@ -154,6 +175,108 @@ emm_status emm_decode_attn(const emm_batch* b, const void* q, const void* k_cach
 {
     if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
     return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1);
+}
+
+emm_status emm_decode_attn_shared_workspace_size(const emm_batch* b, const emm_shared_prefix* sp, size_t* bytes)
+{
+    if (bytes == nullptr) return EMM_ERR_NULL;
+    *bytes = 0;
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    st = check_supported(b);
+    if (st != EMM_OK) return st;
+    if (sp == nullptr) return EMM_ERR_NULL;
+    if (sp->num_units < 0 || sp->num_units > b->num_reqs / 2 || sp->planned_tiles < 0 || sp->max_own_tiles < 0 ||
+        sp->max_unit_tiles < 0)
+        return EMM_ERR_INVALID_ARG;
+    if (b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
+    const emm::BatchView v = view_of(b);
+    if (b->dtype != EMM_BF16 || !emm::attn_bf16_decode_applies(v)) return EMM_ERR_UNSUPPORTED;
+    *bytes = emm::attn_bf16_decode_shared_workspace_bytes(v, shared_view_of(sp));
+    return EMM_OK;
+}
+
+emm_status emm_decode_attn_shared(const emm_batch* b, const emm_shared_prefix* shared, const void* q,
+                                  const void* k_cache, const void* v_cache, void* out, float* lse, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream)
+{
+    if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
+    return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1, shared);
+}
+
+emm_status emm_shared_prefix_plan_host(const emm_batch* b, const int32_t* pt, const int32_t* prefix,
+                                       const int32_t* new_lens, int32_t min_shared_tokens, int32_t* unit_first_req,
+                                       int32_t* unit_num_reqs, int32_t* unit_shared_len, int32_t* req_unit,
+                                       int32_t* req_shared_len, emm_shared_prefix* shared)
+{
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    if (shared == nullptr) return EMM_ERR_NULL;
+    shared->num_units = shared->planned_tiles = shared->max_own_tiles = shared->max_unit_tiles = 0;
+    if (b->num_reqs == 0) return EMM_OK;
+    if (pt == nullptr || prefix == nullptr || new_lens == nullptr || unit_first_req == nullptr ||
+        unit_num_reqs == nullptr || unit_shared_len == nullptr || req_unit == nullptr || req_shared_len == nullptr)
+        return EMM_ERR_NULL;
+    const int B = b->num_reqs, ps = b->page_size;
+    const int cap = 32 / (b->num_q_heads / b->num_kv_heads);             // requests whose rows fit one MFMA tile
+    const int floor_len = min_shared_tokens < 32 ? 32 : min_shared_tokens;
+    for (int r = 0; r < B; ++r) {
+        req_unit[r] = -1;
+        req_shared_len[r] = 0;
+    }
+    // tokens that requests i and j share: leading equal page-table entries, counted only as far as both
+    // requests' cached tokens fill the page
+    auto common = [&](int i, int j) -> int64_t {
+        const int64_t full = std::min(prefix[i], prefix[j]) / ps;
+        const int32_t* a = pt + static_cast<int64_t>(i) * b->max_pages_per_req;
+        const int32_t* c = pt + static_cast<int64_t>(j) * b->max_pages_per_req;
+        int64_t p = 0;
+        while (p < full && p < b->max_pages_per_req && a[p] == c[p]) ++p;
+        return p * ps;
+    };
+    int U = 0;
+    for (int i = 0; i < B;) {
+        int n = 1;
+        int64_t shared = 0;
+        if (new_lens[i] == 1 && cap >= 2) {
+            int64_t cur = INT64_MAX;
+            for (int j = i + 1; j < B && n < cap && new_lens[j] == 1; ++j) {
+                const int64_t cand = std::min(cur, common(i, j)) / 32 * 32;
+                // one more request pays if the keys saved, shared * (requests - 1), do not go down
+                if (cand < floor_len || (n > 1 && cand * n < shared * (n - 1))) break;
+                cur = shared = cand;
+                ++n;
+            }
+        }
+        if (n >= 2) {
+            unit_first_req[U] = i;
+            unit_num_reqs[U] = n;
+            unit_shared_len[U] = static_cast<int32_t>(shared);
+            for (int r = i; r < i + n; ++r) {
+                req_unit[r] = U;
+                req_shared_len[r] = static_cast<int32_t>(shared);
+            }
+            ++U;
+        }
+        i += n;
+    }
+    shared->num_units = U;
+    int64_t tiles = 0, own_max = 0, unit_max = 0;
+    for (int u = 0; u < U; ++u) {
+        tiles += unit_shared_len[u] / 32;
+        unit_max = std::max<int64_t>(unit_max, unit_shared_len[u] / 32);
+    }
+    for (int r = 0; r < B; ++r)
+        if (new_lens[r] > 0) {
+            // a decode query sees its cached tokens and itself; its own part starts behind the unit's
+            const int64_t own = (static_cast<int64_t>(prefix[r]) + new_lens[r] + 31) / 32 - req_shared_len[r] / 32;
+            tiles += own;
+            own_max = std::max(own_max, own);
+        }
+    shared->planned_tiles = static_cast<int32_t>(std::min<int64_t>(tiles, INT32_MAX));
+    shared->max_own_tiles = static_cast<int32_t>(std::max<int64_t>(own_max, 1));
+    shared->max_unit_tiles = static_cast<int32_t>(unit_max);
+    return EMM_OK;
 }
 
 emm_status emm_cross_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,

@@ -17,6 +17,14 @@
 //   merge 2   = a pair with several pieces leaves one record per piece in the workspace and
 //               attn_bf16_decode_merge_kernel combines them; a pair with one piece writes its output
 //               directly.  Both kernels derive the piece count from the lengths, nothing is exchanged.
+//
+// Shared prefixes (Section 3.3: requests repeat system prompts and images).  Requests whose leading pages
+// are the same physical pages can be given as a UNIT: up to 32 / G consecutive requests and the length they
+// share.  The shared keys are then read once per unit instead of once per request: extra workgroups at the
+// end of the grid take the shared part, with the query rows of all the unit's requests side by side in the
+// 32 columns of the MFMA, while the requests' own workgroups start behind the shared part; the merge
+// kernel adds the records of both.  Built as a second instantiation (SHARED) so that the plain path pays
+// nothing for it.
 #include "attn_bf16_common.h"
 
 namespace emm {
@@ -36,13 +44,16 @@ constexpr int AHEAD = 2;                         // tiles in flight beyond the o
 constexpr int MIN_TILES_PER_PIECE = 4, MAX_TILES_PER_PIECE = 60;   // 60 + AHEAD page ids fit the 64 lanes
 constexpr int WORKGROUPS_PER_ROUND = 3 * 256;     // three workgroups on each of 256 CUs
 constexpr int OVERHEAD_TILES = 4;                // start and finish of a workgroup, in tile times
+constexpr int MAX_ROWS = 32;                     // query rows of a shared-prefix unit: the MFMA's columns
 static_assert(NW * MAX_G * REC_FLOATS * 4 <= 2 * NSLOT * TILE_BYTES, "the merge across waves reuses the tile rings");
 static_assert(AHEAD == NSLOT - 1, "the slot refilled in iteration i is the one read in iteration i-1");
 
 struct DecodeShape {
     int n_pairs;            // (request, KV head) pairs
+    int n_unit_pairs;       // (shared-prefix unit, KV head) pairs
     int tiles_per_piece;    // 32-key tiles per workgroup
     int pieces_max;         // workgroups per pair in the grid (a pair uses as many as its context needs)
+    int pieces_unit;        // workgroups per (unit, KV head) pair in the grid
 };
 
 __device__ inline int pieces_of(int kv_len, int tiles_per_piece)
@@ -50,32 +61,64 @@ __device__ inline int pieces_of(int kv_len, int tiles_per_piece)
     const int n_tiles = (kv_len + BK - 1) / BK;
     return n_tiles == 0 ? 1 : (n_tiles + tiles_per_piece - 1) / tiles_per_piece;
 }
+// pieces of a request's own part when its first t_off tiles belong to a unit's shared part: possibly none
+__device__ inline int own_pieces_of(int kv_len, int t_off, int tiles_per_piece, bool in_unit)
+{
+    if (!in_unit) return pieces_of(kv_len, tiles_per_piece);
+    const int n_tiles = (kv_len + BK - 1) / BK - t_off;
+    return n_tiles <= 0 ? 0 : (n_tiles + tiles_per_piece - 1) / tiles_per_piece;
+}
+// workspace: the requests' own records first, [pair][piece][MAX_G rows], then the units', [unit][KV head][piece][MAX_ROWS]
+__device__ __host__ inline size_t unit_records_offset(const DecodeShape& S)
+{
+    return (size_t)S.n_pairs * S.pieces_max * MAX_G * REC_FLOATS;
+}
 
-template <bool CAUSAL>
-__global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, DecodeShape S)
+template <bool CAUSAL, bool SHARED>
+__global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, DecodeShape S, SharedPrefixView sv)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NSLOT * TILE_BYTES];   // K ring, then V ring
     constexpr int V_SM = NSLOT * TILE_BYTES;
 
     const BatchView& b = a.b;
     const int G = b.num_q_heads / b.num_kv_heads;
-    const int pair = blockIdx.x / S.pieces_max, piece = blockIdx.x % S.pieces_max;
+    const int n_own_blocks = S.n_pairs * S.pieces_max;
+    const bool unit_mode = SHARED && (int)blockIdx.x >= n_own_blocks;     // this workgroup: a unit's shared part
+    const int blk = unit_mode ? blockIdx.x - n_own_blocks : blockIdx.x;
+    // piece-major: the first pieces of all contexts come first in the grid, the workgroups that find their
+    // context too short for their piece number (they exit at once) gather at its end
+    const int n_items = unit_mode ? S.n_unit_pairs : S.n_pairs;
+    const int pair = blk % n_items, piece = blk / n_items;                // unit mode: pair = (unit, KV head)
     const int kvh = pair % b.num_kv_heads;
-    const int r = pair / b.num_kv_heads;
+    const int unit = pair / b.num_kv_heads;
+    const int r = unit_mode ? sv.unit_first_req[unit] : unit;             // the request whose page table is read
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    const int t_begin = piece * S.tiles_per_piece;
+    const int t_off = (SHARED && !unit_mode) ? sv.req_shared_len[r] / BK : 0;   // tiles a unit computes for this request
+    const int t_begin = t_off + piece * S.tiles_per_piece;
     // lane k of a wave holds the physical page this wave fetches for tile t_begin + k (a piece has at most
     // 60 tiles and fetches run two tiles ahead, so 64 lanes cover it).  Asked for before the lengths are
     // known, so that the two loads overlap: entries past the request's pages are read (the row has
     // max_pages of them) and whatever they hold is forced into the pool; those keys are masked.
     const int32_t* __restrict__ pt = b.page_table + (long long)r * b.max_pages;
     const int pg_raw = b.max_pages > 0 ? pt[min((t_begin + lane) * 2 + (wave >> 1), b.max_pages - 1)] : 0;
-    if (b.new_lens[r] <= 0) return;                          // no query token
-    const int P = b.prefix_lens[r];
-    const int kv_len = CAUSAL ? P + 1 : P;                   // keys the query sees = slots that hold tokens
-    const int n_pieces = pieces_of(kv_len, S.tiles_per_piece);
+    int kv_len, n_pieces, n_rows;
+    bool direct;                                             // one piece and no unit: this workgroup writes the output
+    if (!unit_mode) {
+        if (b.new_lens[r] <= 0) return;                      // no query token
+        const int P = b.prefix_lens[r];
+        kv_len = CAUSAL ? P + 1 : P;                         // keys the query sees = slots that hold tokens
+        const bool in_unit = SHARED && sv.req_unit[r] >= 0;
+        n_pieces = own_pieces_of(kv_len, t_off, S.tiles_per_piece, in_unit);
+        n_rows = G;
+        direct = n_pieces == 1 && !in_unit;
+    } else {
+        kv_len = sv.unit_shared_len[unit];                   // a multiple of the tile: no mask, no ragged tail
+        n_pieces = (kv_len / BK + S.tiles_per_piece - 1) / S.tiles_per_piece;
+        n_rows = min(sv.unit_num_reqs[unit] * G, MAX_ROWS);
+        direct = false;
+    }
     if (piece >= n_pieces) return;
     const int n_tiles_all = (kv_len + BK - 1) / BK;
     const int n_tiles = min(S.tiles_per_piece, n_tiles_all - t_begin);     // 0 only for an empty context
@@ -83,10 +126,13 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int l32 = lane & 31, h32 = lane >> 5;
     const int limit = kv_len - 1;                            // last visible key (the query's own slot if causal)
     const int n_clear = kv_len / BK;                         // tiles 0 .. n_clear-1 need no mask
-    const long long q_row = b.cu_new_lens[r];
 
-    // every wave holds the same G query rows; columns G..31 of the MFMA repeat row G-1 and are discarded
-    const int hq = kvh * G + min(l32, G - 1);
+    // every wave holds the same query rows: the G heads of the request, or in unit mode the G heads of each
+    // of the unit's requests; the remaining columns of the MFMA repeat the last row and are discarded
+    const int my_row = min(l32, n_rows - 1);
+    const int my_req = unit_mode ? r + my_row / G : r;
+    const int hq = kvh * G + (unit_mode ? my_row % G : my_row);
+    const long long q_row = min((long long)b.cu_new_lens[my_req], (long long)b.total_new_tokens - 1);
     const __bf16* __restrict__ qp = (const __bf16*)a.q + (q_row * b.num_q_heads + hq) * D + 8 * h32;
     bf16x8 qf[8];
 #pragma unroll
@@ -212,45 +258,52 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     }
     __syncthreads();                                         // every wave's fetches have landed, every read is done
 
-    // ---- merge 1: the waves' partial results for the G rows, through LDS (the rings are free now)
-    float* __restrict__ red = (float*)smem;                  // [NW waves][G rows][130]
+    // ---- merge 1: the waves' partial results, 16 rows at a time, through LDS (the rings are free now)
+    float* __restrict__ red = (float*)smem;                  // [NW waves][16 rows][130]
     const float l_pair = pair_sum(l_run);
-    if (l32 < G) {
-        float* dst = red + (wave * G + l32) * REC_FLOATS;
+    float* __restrict__ rec =
+        unit_mode ? (float*)a.workspace + unit_records_offset(S) + (size_t)(pair * S.pieces_unit + piece) * MAX_ROWS * REC_FLOATS
+                  : (float*)a.workspace + (size_t)(pair * S.pieces_max + piece) * MAX_G * REC_FLOATS;
+    for (int row0 = 0; row0 < n_rows; row0 += MAX_G) {
+        if (row0 > 0) __syncthreads();                       // the pass before has been read
+        const int rows_here = min(MAX_G, n_rows - row0);
+        if (l32 >= row0 && l32 < row0 + rows_here) {
+            float* dst = red + (wave * MAX_G + l32 - row0) * REC_FLOATS;
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+            for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dst[32 * nb + 8 * (v >> 2) + 4 * h32 + (v & 3)] = o_acc[nb][v];
-        if (h32 == 0) {
-            dst[D] = m_run;
-            dst[D + 1] = l_pair;
+                for (int v = 0; v < 16; ++v) dst[32 * nb + 8 * (v >> 2) + 4 * h32 + (v & 3)] = o_acc[nb][v];
+            if (h32 == 0) {
+                dst[D] = m_run;
+                dst[D + 1] = l_pair;
+            }
         }
-    }
-    __syncthreads();
-    float* __restrict__ rec = (float*)a.workspace + (size_t)(pair * S.pieces_max + piece) * MAX_G * REC_FLOATS;
-    for (int idx = tid; idx < G * D; idx += NT) {
-        const int row = idx / D, ch = idx % D;
-        float m_all = -INFINITY;
+        __syncthreads();
+        for (int idx = tid; idx < rows_here * D; idx += NT) {
+            const int lrow = idx / D, ch = idx % D, row = row0 + lrow;
+            float m_all = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) m_all = fmaxf(m_all, red[(w * G + row) * REC_FLOATS + D]);
-        float acc = 0.f, l_tot = 0.f;
+            for (int w = 0; w < NW; ++w) m_all = fmaxf(m_all, red[(w * MAX_G + lrow) * REC_FLOATS + D]);
+            float acc = 0.f, l_tot = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float* src = red + (w * G + row) * REC_FLOATS;
-            const float wgt = (src[D] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((src[D] - m_all) * c_log2);
-            acc += wgt * src[ch];
-            l_tot += wgt * src[D + 1];
-        }
-        if (n_pieces == 1) {
-            const int head = kvh * G + row;
-            ((__bf16*)a.out)[(q_row * b.num_q_heads + head) * D + ch] = (__bf16)(l_tot > 0.f ? acc / l_tot : 0.f);
-            if (ch == 0 && a.lse != nullptr)
-                a.lse[q_row * b.num_q_heads + head] = (l_tot > 0.f) ? m_all * b.softmax_scale + logf(l_tot) : -INFINITY;
-        } else {
-            rec[row * REC_FLOATS + ch] = acc;
-            if (ch == 0) {
-                rec[row * REC_FLOATS + D] = m_all;
-                rec[row * REC_FLOATS + D + 1] = l_tot;
+            for (int w = 0; w < NW; ++w) {
+                const float* src = red + (w * MAX_G + lrow) * REC_FLOATS;
+                const float wgt = (src[D] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((src[D] - m_all) * c_log2);
+                acc += wgt * src[ch];
+                l_tot += wgt * src[D + 1];
+            }
+            if (direct) {
+                const int head = kvh * G + row;
+                const long long q_own = b.cu_new_lens[r];
+                ((__bf16*)a.out)[(q_own * b.num_q_heads + head) * D + ch] = (__bf16)(l_tot > 0.f ? acc / l_tot : 0.f);
+                if (ch == 0 && a.lse != nullptr)
+                    a.lse[q_own * b.num_q_heads + head] = (l_tot > 0.f) ? m_all * b.softmax_scale + logf(l_tot) : -INFINITY;
+            } else {
+                rec[row * REC_FLOATS + ch] = acc;
+                if (ch == 0) {
+                    rec[row * REC_FLOATS + D] = m_all;
+                    rec[row * REC_FLOATS + D + 1] = l_tot;
+                }
             }
         }
     }
@@ -274,8 +327,8 @@ __device__ inline float wave_sum64(float x)
     return x;
 }
 
-template <bool CAUSAL>
-__global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(AttnArgs a, DecodeShape S)
+template <bool CAUSAL, bool SHARED>
+__global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(AttnArgs a, DecodeShape S, SharedPrefixView sv)
 {
     __shared__ float w_s[MERGE_THREADS], part_s[MERGE_THREADS / 64], acc_s[D];
     const BatchView& b = a.b;
@@ -285,17 +338,29 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(A
     const int r = pair / b.num_kv_heads;
     if (b.new_lens[r] <= 0) return;
     const int P = b.prefix_lens[r];
-    const int n_pieces = pieces_of(CAUSAL ? P + 1 : P, S.tiles_per_piece);
-    if (n_pieces == 1) return;
+    // the records of this row: n_own from the request's own workgroups, then n_unit from its unit's
+    const int unit = SHARED ? sv.req_unit[r] : -1;
+    const int n_own = own_pieces_of(CAUSAL ? P + 1 : P, SHARED ? sv.req_shared_len[r] / BK : 0, S.tiles_per_piece, unit >= 0);
+    if (unit < 0 && n_own == 1) return;
+    int n_unit = 0;
+    const float* __restrict__ rec_unit = nullptr;
+    if (unit >= 0) {
+        n_unit = (sv.unit_shared_len[unit] / BK + S.tiles_per_piece - 1) / S.tiles_per_piece;
+        rec_unit = (const float*)a.workspace + unit_records_offset(S) +
+                   ((size_t)(unit * b.num_kv_heads + kvh) * S.pieces_unit * MAX_ROWS + (r - sv.unit_first_req[unit]) * G + row) * REC_FLOATS;
+    }
+    const int n_pieces = n_own + n_unit;
     const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
     const int tid = threadIdx.x, ch = tid % D, half = tid / D, wave = tid >> 6;
-    const float* __restrict__ rec0 =
+    const float* __restrict__ rec_own =
         (const float*)a.workspace + ((size_t)pair * S.pieces_max * MAX_G + row) * REC_FLOATS;
-    constexpr size_t STEP = (size_t)MAX_G * REC_FLOATS;     // floats from one piece's record of a row to the next
+    auto record = [&](int j) -> const float* {               // this row in record j
+        return j < n_own ? rec_own + (size_t)j * (MAX_G * REC_FLOATS) : rec_unit + (size_t)(j - n_own) * (MAX_ROWS * REC_FLOATS);   // consecutive pieces of the unit
+    };
 
     // the maximum over all pieces (every piece of a context that needs several has a visible key)
     float m_all = -INFINITY;
-    for (int j = tid; j < n_pieces; j += MERGE_THREADS) m_all = fmaxf(m_all, rec0[j * STEP + D]);
+    for (int j = tid; j < n_pieces; j += MERGE_THREADS) m_all = fmaxf(m_all, record(j)[D]);
     m_all = wave_max64(m_all);
     if ((tid & 63) == 0) part_s[wave] = m_all;
     __syncthreads();
@@ -305,16 +370,15 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(A
     for (int c0 = 0; c0 < n_pieces; c0 += MERGE_THREADS) {
         __syncthreads();                                     // the weights of the chunk before have been used
         if (c0 + tid < n_pieces) {
-            const float* src = rec0 + (size_t)(c0 + tid) * STEP;
+            const float* src = record(c0 + tid);
             const float wgt = __builtin_amdgcn_exp2f((src[D] - m_all) * c_log2);
             w_s[tid] = wgt;
             l_tot += wgt * src[D + 1];
         }
         __syncthreads();
         const int n = min(MERGE_THREADS, n_pieces - c0);
-        const float* src = rec0 + (size_t)c0 * STEP + ch;
 #pragma unroll 8
-        for (int j = half; j < n; j += 2) acc += w_s[j] * src[j * STEP];
+        for (int j = half; j < n; j += 2) acc += w_s[j] * record(c0 + j)[ch];
     }
     l_tot = wave_sum64(l_tot);
     __syncthreads();                                         // part_s is read above
@@ -332,30 +396,46 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(A
     }
 }
 
-// How a decode batch is cut.  The host knows the longest possible context only (the width of the page
-// table), so it plans for `n_pairs` contexts of that length: workgroups run in rounds of
-// WORKGROUPS_PER_ROUND, a round lasts as long as its longest piece plus the fixed cost of starting and
-// finishing a workgroup (about OVERHEAD_TILES tiles' worth), and the piece length with the least total is
-// taken -- in particular one that makes the last round a full one.
-DecodeShape decode_shape(const BatchView& b)
+// How a decode batch is cut.  Workgroups run in rounds of WORKGROUPS_PER_ROUND, a round lasts as long as its
+// longest piece plus the fixed cost of starting and finishing a workgroup (about OVERHEAD_TILES tiles'
+// worth), every workgroup of the grid, also one that finds nothing to do, costs the dispatcher about 1/128 of a
+// tile time, and the piece length with the least total is taken -- in particular one that makes the last
+// round a full one.  (Sweeps of the piece length on uniform batches put the optimum where this model puts it;
+// finer models of HBM saturation and of ragged batches were tried and predicted no better.)
+// What the host is told (SharedPrefixView) sharpens the plan: `max_own_tiles` / `max_unit_tiles` bound the
+// longest own part / shared part and with it the pieces per context that the grid must provide, and when
+// units take work away `planned_tiles` is the amount that is left (32-key tiles per KV head, summed over
+// contexts).  Without them the host knows only the longest possible context (the width of the page table) and
+// plans for every context being that long.
+DecodeShape decode_shape(const BatchView& b, const SharedPrefixView& sv = SharedPrefixView{})
 {
     DecodeShape S;
     S.n_pairs = b.num_reqs * b.num_kv_heads;
-    const long long max_tiles = ((long long)b.max_pages * 16 + BK - 1) / BK;
+    S.n_unit_pairs = sv.num_units * b.num_kv_heads;
+    const long long table_tiles = ((long long)b.max_pages * 16 + BK - 1) / BK;       // longest possible context
+    const long long own_tiles = sv.max_own_tiles > 0 ? std::min<long long>(sv.max_own_tiles, table_tiles) : table_tiles;
+    const long long unit_tiles = sv.num_units == 0 ? 0
+                                 : sv.max_unit_tiles > 0 ? std::min<long long>(sv.max_unit_tiles, table_tiles) : table_tiles;
+    const long long items = (long long)S.n_pairs + S.n_unit_pairs;
+    auto pieces = [](long long tiles, int tpp) { return tiles > 0 ? (tiles + tpp - 1) / tpp : 1; };
     long long best_cost = -1;
     int best = MIN_TILES_PER_PIECE;
     for (int tpp = MIN_TILES_PER_PIECE; tpp <= MAX_TILES_PER_PIECE; ++tpp) {
-        const long long pieces = max_tiles > 0 ? (max_tiles + tpp - 1) / tpp : 1;
-        const long long rounds = (S.n_pairs * pieces + WORKGROUPS_PER_ROUND - 1) / WORKGROUPS_PER_ROUND;
-        const long long cost = rounds * (tpp + OVERHEAD_TILES);
+        const long long grid = S.n_pairs * pieces(own_tiles, tpp) + S.n_unit_pairs * pieces(unit_tiles, tpp);
+        // known total: half a piece lost per context; else every context as long as the longest
+        const long long wgs = (sv.planned_tiles > 0 && sv.num_units > 0)
+                                  ? std::min(grid, ((long long)sv.planned_tiles * b.num_kv_heads + tpp - 1) / tpp + items / 2)
+                                  : grid;
+        const long long rounds = (wgs + WORKGROUPS_PER_ROUND - 1) / WORKGROUPS_PER_ROUND;
+        const long long cost = 128 * rounds * (tpp + OVERHEAD_TILES) + grid;         // in 1/128 tile times
         if (best_cost < 0 || cost <= best_cost) {            // ties: the longer piece, fewer records to merge
             best_cost = cost;
             best = tpp;
         }
     }
     S.tiles_per_piece = best;
-    S.pieces_max = (int)((max_tiles + best - 1) / best);
-    if (S.pieces_max < 1) S.pieces_max = 1;
+    S.pieces_max = (int)pieces(own_tiles, best);
+    S.pieces_unit = (int)pieces(unit_tiles, best);
     return S;
 }
 
@@ -372,25 +452,50 @@ size_t attn_bf16_decode_workspace_bytes(const BatchView& b)
     return (size_t)S.n_pairs * S.pieces_max * MAX_G * REC_FLOATS * sizeof(float);
 }
 
-hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream)
+size_t attn_bf16_decode_shared_workspace_bytes(const BatchView& b, const SharedPrefixView& sv)
+{
+    const DecodeShape S = decode_shape(b, sv);
+    return (unit_records_offset(S) + (size_t)S.n_unit_pairs * S.pieces_unit * MAX_ROWS * REC_FLOATS) * sizeof(float);
+}
+
+namespace {
+
+template <bool SHARED>
+hipError_t launch_decode(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream)
 {
     const BatchView& b = a.b;
     if (b.total_new_tokens == 0 || b.num_reqs == 0) return hipSuccess;
-    const DecodeShape S = decode_shape(b);
-    const long long grid = (long long)S.n_pairs * S.pieces_max;
+    const DecodeShape S = decode_shape(b, sv);
+    // the requests' own workgroups first, then (SHARED) those of the units' shared parts
+    const long long grid = (long long)S.n_pairs * S.pieces_max + (long long)S.n_unit_pairs * S.pieces_unit;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)
-        hipLaunchKernelGGL(attn_bf16_decode_kernel<true>, dim3((unsigned)grid), dim3(NT), 0, stream, a, S);
+        hipLaunchKernelGGL((attn_bf16_decode_kernel<true, SHARED>), dim3((unsigned)grid), dim3(NT), 0, stream, a, S, sv);
     else
-        hipLaunchKernelGGL(attn_bf16_decode_kernel<false>, dim3((unsigned)grid), dim3(NT), 0, stream, a, S);
+        hipLaunchKernelGGL((attn_bf16_decode_kernel<false, SHARED>), dim3((unsigned)grid), dim3(NT), 0, stream, a, S, sv);
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess || S.pieces_max == 1) return err;
+    if (err != hipSuccess || (!SHARED && S.pieces_max == 1)) return err;   // one piece each: already written
     const int G = b.num_q_heads / b.num_kv_heads;
     if (a.causal)
-        hipLaunchKernelGGL(attn_bf16_decode_merge_kernel<true>, dim3((unsigned)(S.n_pairs * G)), dim3(MERGE_THREADS), 0, stream, a, S);
+        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<true, SHARED>), dim3((unsigned)(S.n_pairs * G)),
+                           dim3(MERGE_THREADS), 0, stream, a, S, sv);
     else
-        hipLaunchKernelGGL(attn_bf16_decode_merge_kernel<false>, dim3((unsigned)(S.n_pairs * G)), dim3(MERGE_THREADS), 0, stream, a, S);
+        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<false, SHARED>), dim3((unsigned)(S.n_pairs * G)),
+                           dim3(MERGE_THREADS), 0, stream, a, S, sv);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream)
+{
+    return launch_decode<false>(a, SharedPrefixView{}, stream);
+}
+
+hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream)
+{
+    // without units only the bounds matter: the plain kernels, cut by the sharper plan
+    return sv.num_units > 0 ? launch_decode<true>(a, sv, stream) : launch_decode<false>(a, sv, stream);
 }
 
 }  // namespace emm

@@ -29,6 +29,19 @@ struct AttnArgs {
     void* workspace;      // scratch for the bf16 kernel's cut units, or nullptr
 };
 
+// Shared-prefix units of a decode batch (device arrays; see emm_shared_prefix in emm.h)
+struct SharedPrefixView {
+    const int32_t* unit_first_req;   // [U]
+    const int32_t* unit_num_reqs;    // [U]
+    const int32_t* unit_shared_len;  // [U] multiple of 32
+    const int32_t* req_unit;         // [B] or -1
+    const int32_t* req_shared_len;   // [B] or 0
+    int32_t num_units;
+    int32_t planned_tiles;           // host hint: 32-key tiles per KV head over the whole batch, 0 = unknown
+    int32_t max_own_tiles;           // bound on a request's own part in tiles, 0 = the page table's width
+    int32_t max_unit_tiles;          // bound on a unit's shared part in tiles, 0 = the page table's width
+};
+
 // Each launcher enqueues on `stream` and returns the launch status.
 hipError_t launch_kv_scatter(const BatchView& b, const void* k_new, const void* v_new, void* k_cache,
                              void* v_cache, int elt_bytes, hipStream_t stream);
@@ -39,5 +52,8 @@ size_t attn_bf16_d128_workspace_bytes();   // what launch_attn_bf16_d128 wants b
 bool attn_bf16_decode_applies(const BatchView& b);
 size_t attn_bf16_decode_workspace_bytes(const BatchView& b);
 hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream);
+// the same with shared-prefix units (sv.num_units >= 1)
+size_t attn_bf16_decode_shared_workspace_bytes(const BatchView& b, const SharedPrefixView& sv);
+hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream);
 
 }  // namespace emm

@@ -306,7 +306,13 @@ def decode_config(name: str, shrink: int = 1) -> Workload:
     prefill workloads leave behind.
       decode_video_b8   8 requests with the video context of config 3 (16384 + 2048 tokens), 28/4 heads
       decode_mixed_b32  the 32 requests of config 4 after their prefill (context = prefix + new), 32/8 heads
-      decode_b64_8k     64 requests of 8192 tokens, 28/4 heads"""
+      decode_b64_8k     64 requests of 8192 tokens, 28/4 heads
+    and two with shared prefix pages (requests about the same video / the same system prompt and image):
+      decode_shared_video_b8   as decode_video_b8, the 16384 video tokens in pages common to all 8 requests
+      decode_shared_video_b32  8 videos with 4 requests each (402 MB of distinct K/V: more than the caches hold)
+      decode_shared_image_b32  32 requests in 4 groups of 8, each group sharing 2880 tokens (system prompt +
+                               image), then 200..1500 private tokens, 32/8 heads"""
+    share_group = shared_len = None
     if name == "decode_video_b8":
         ctx, H, Hkv, seed = [_s(16384 + 2048, shrink)] * 8, 28, 4, 2001
     elif name == "decode_mixed_b32":
@@ -314,13 +320,27 @@ def decode_config(name: str, shrink: int = 1) -> Workload:
         ctx, H, Hkv, seed = [int(p) + int(n) for p, n in zip(c4.prefix_lens, c4.new_lens)], 32, 8, 2002
     elif name == "decode_b64_8k":
         ctx, H, Hkv, seed = [_s(8192, shrink)] * 64, 28, 4, 2003
+    elif name == "decode_shared_video_b8":
+        ctx, H, Hkv, seed = [_s(16384 + 2048, shrink)] * 8, 28, 4, 2004
+        share_group, shared_len = [0] * 8, [_s(16384, shrink)] * 8
+    elif name == "decode_shared_video_b32":
+        ctx, H, Hkv, seed = [_s(16384 + 2048, shrink)] * 32, 28, 4, 2006
+        share_group, shared_len = [r // 4 for r in range(32)], [_s(16384, shrink)] * 32
+    elif name == "decode_shared_image_b32":
+        rng = np.random.default_rng(np.random.PCG64(2005 + 7919))
+        shared = _s(2880, shrink)
+        ctx = [shared + _s(int(rng.integers(200, 1501)), shrink) for _ in range(32)]
+        H, Hkv, seed = 32, 8, 2005
+        share_group, shared_len = [r // 8 for r in range(32)], [shared] * 32
     else:
         raise KeyError(name)
     return build_workload(name, "causal", "bf16", seed, num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
-                          page_size=16, prefix_lens=ctx, new_lens=[1] * len(ctx), spare_pages=8)
+                          page_size=16, prefix_lens=ctx, new_lens=[1] * len(ctx), share_group=share_group,
+                          shared_len=shared_len, spare_pages=8)
 
 
 DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k")
+DECODE_SHARED_CONFIGS = ("decode_shared_video_b8", "decode_shared_video_b32", "decode_shared_image_b32")
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 

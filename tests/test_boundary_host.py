@@ -153,3 +153,73 @@ def test_validate_rejects_broken_batches():
     prefix = wl.prefix_lens.copy()
     prefix[0] += 16 * wl.max_pages_per_req
     assert B.emm_validate_batch_host(b, *args(prefix=prefix)) == B.EMM_ERR_INVALID_ARG
+
+
+def test_shared_prefix_plan_host():
+    """Units found from host copies of the page tables: consecutive requests, whole shared pages that both
+    requests' cached tokens fill, multiples of 32 tokens, at most 32 / G requests, never fewer keys saved."""
+    def plan(pt, prefix, new, H=28, Hkv=4, min_shared=32):
+        pt = np.asarray(pt, dtype=np.int32)
+        b = _batch(num_reqs=pt.shape[0], num_q_heads=H, num_kv_heads=Hkv, num_pages=1000, max_pages_per_req=pt.shape[1],
+                   total_new_tokens=int(sum(new)), max_new_len=max(new))
+        return B.emm_shared_prefix_plan_host(b, pt, np.asarray(prefix, np.int32), np.asarray(new, np.int32), min_shared)
+
+    base = list(range(100, 140))                                     # 40 pages = 640 tokens
+    def row(n_shared, tag):
+        return base[:n_shared] + [500 + 40 * tag + i for i in range(40 - n_shared)]
+    # three requests share 10 pages (160 tokens), a fourth shares nothing, then two share 3 pages (48 -> 32 tokens)
+    pt = [row(10, 0), row(10, 1), row(10, 2), [900 + i for i in range(40)],
+          [700, 701, 702] + [600 + i for i in range(37)], [700, 701, 702] + [650 + i for i in range(37)]]
+    p = plan(pt, [300, 200, 640, 640, 100, 100], [1] * 6)
+    assert p["num_units"] == 2
+    assert p["unit_first_req"].tolist() == [0, 4] and p["unit_num_reqs"].tolist() == [3, 2]
+    assert p["unit_shared_len"].tolist() == [160, 32]
+    assert p["req_unit"].tolist() == [0, 0, 0, -1, 1, 1] and p["req_shared_len"].tolist() == [160, 160, 160, 0, 32, 32]
+    # tiles: units 160/32 + 32/32, own parts ceil((P + 1 - shared) / 32) = 5, 2, 16, 21, 3, 3
+    assert p["planned_tiles"] == 5 + 1 + 5 + 2 + 16 + 21 + 3 + 3
+    assert p["max_own_tiles"] == 21 and p["max_unit_tiles"] == 5
+    # cached tokens limit the shared length: the second request has only 70 tokens in its pages -> 64
+    p = plan(pt[:2], [300, 70], [1, 1])
+    assert p["unit_shared_len"].tolist() == [64]
+    # below the floor: no unit
+    assert plan(pt[:2], [300, 70], [1, 1], min_shared=128)["num_units"] == 0
+    assert plan(pt[4:], [100, 20], [1, 1])["num_units"] == 0        # 16 common tokens < 32
+    # a request without a new token ends a unit; G = 7 allows 4 requests per unit
+    pt8 = [row(20, i) for i in range(8)]
+    p = plan(pt8, [640] * 8, [1, 1, 0, 1, 1, 1, 1, 1])
+    assert p["unit_first_req"].tolist() == [0, 3] and p["unit_num_reqs"].tolist() == [2, 4]
+    assert p["req_unit"].tolist() == [0, 0, -1, 1, 1, 1, 1, -1]
+    # G = 4: 8 per unit; G = 32: no units possible
+    assert plan(pt8, [640] * 8, [1] * 8, H=32, Hkv=8)["unit_num_reqs"].tolist() == [8]
+    assert plan(pt8, [640] * 8, [1] * 8, H=32, Hkv=1)["num_units"] == 0
+    # a request that shares much less is left out when it would lower the keys saved: 320 * 1 > 32 * 2
+    pt3 = [row(20, 0), row(20, 1), row(2, 2)]
+    p = plan(pt3, [640] * 3, [1] * 3)
+    assert p["unit_num_reqs"].tolist() == [2] and p["unit_shared_len"].tolist() == [320] and p["req_unit"].tolist() == [0, 0, -1]
+
+
+def test_decode_shared_argument_checks():
+    lib = B.load()
+    n = ctypes.c_size_t(0)
+    b = _batch(num_reqs=4, total_new_tokens=4, max_new_len=1)
+
+    def size(batch, **kw):
+        sp = B.make_shared_prefix(**kw)
+        return lib.emm_decode_attn_shared_workspace_size(ctypes.byref(batch), ctypes.byref(sp), ctypes.byref(n)), n.value
+
+    plain = B.emm_prefill_attn_workspace_size(b)
+    st, with_units = size(b, num_units=2)
+    assert st == B.EMM_OK and with_units > plain
+    assert size(b, num_units=0) == (B.EMM_OK, plain)
+    st, tight = size(b, num_units=2, planned_tiles=6, max_own_tiles=1, max_unit_tiles=1)
+    assert st == B.EMM_OK and 0 < tight <= with_units
+    assert size(b, num_units=3)[0] == B.EMM_ERR_INVALID_ARG
+    assert size(b, num_units=-1)[0] == B.EMM_ERR_INVALID_ARG
+    assert size(b, num_units=1, planned_tiles=-5)[0] == B.EMM_ERR_INVALID_ARG
+    assert size(b, num_units=1, max_own_tiles=-1)[0] == B.EMM_ERR_INVALID_ARG
+    assert size(_batch(num_reqs=4, total_new_tokens=8, max_new_len=2), num_units=1)[0] == B.EMM_ERR_INVALID_ARG
+    assert size(_batch(num_reqs=4, total_new_tokens=4, max_new_len=1, num_q_heads=34, num_kv_heads=2),
+                num_units=1)[0] == B.EMM_ERR_UNSUPPORTED
+    sp = B.make_shared_prefix(num_units=1)
+    assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), ctypes.byref(sp), None) == B.EMM_ERR_NULL
+    assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), None, ctypes.byref(n)) == B.EMM_ERR_NULL

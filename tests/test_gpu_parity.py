@@ -207,6 +207,49 @@ def test_decode_step_parity(name, kind, H, Hkv, ctx, new):
         assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
 
 
+SHARED_CASES = [
+    # name, H, Hkv, context lengths, new lens, share group per request, shared tokens per request, units expected
+    ("shared_pairs", 28, 4, [700, 650, 900, 300, 1300], [1] * 5, [0, 0, 1, 2, 2], [512, 512, 0, 290, 290], 2),
+    ("shared_wide", 32, 8, [2100 + 37 * i for i in range(19)], [1] * 19, [0] * 19, [2048] * 19, 3),   # 8 + 8 + 3 requests
+    ("shared_g16", 16, 1, [800, 801, 400], [1, 1, 1], [0, 0, 0], [384, 384, 384], 1),      # two requests fill a tile
+    ("shared_g1", 8, 8, [100 * i + 640 for i in range(12)], [1] * 12, [0] * 12, [640] * 12, 1),
+    ("shared_exact", 28, 4, [1024, 1024, 1024], [1, 1, 1], [0, 0, 0], [1024, 1024, 1024], 1),   # own part: the new token only
+    ("shared_holes", 28, 4, [600, 600, 600, 600, 600], [1, 1, 0, 1, 1], [0] * 5, [512] * 5, 2),  # a request without a token
+    ("shared_none", 32, 8, [300, 500], [1, 1], [0, 1], [0, 0], 0),                               # nothing shared
+    ("shared_long", 28, 4, [18432, 18000, 17000, 16500], [1] * 4, [0] * 4, [16384] * 4, 1),      # several pieces per unit
+]
+
+
+@pytest.mark.parametrize("name,H,Hkv,ctx,new,group,shared,n_units", SHARED_CASES)
+def test_decode_shared_prefix_parity(name, H, Hkv, ctx, new, group, shared, n_units):
+    """emm_decode_attn_shared with the units found by emm_shared_prefix_plan_host, against the oracle (which
+    knows nothing of units) and, loosely, against emm_decode_attn on the same batch."""
+    print("case", name, flush=True)
+    wl = W.build_workload(name, "causal", "bf16", 1300 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=ctx, new_lens=new, share_group=group, shared_len=shared)
+    dw = _gpu_run(wl)                                   # scatter + plain decode path
+    plain = as_f64(B.DeviceWorkload.to_numpy_bits(dw.out))
+    plan = dw.plan_shared()
+    print("   units:", plan["num_units"], plan["unit_first_req"].tolist(), plan["unit_num_reqs"].tolist(),
+          plan["unit_shared_len"].tolist(), flush=True)
+    assert plan["num_units"] == n_units
+    dw.out.zero_()
+    dw.lse.zero_()
+    dw.attention_shared()
+    torch.cuda.synchronize()
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+    assert np.abs(as_f64(B.DeviceWorkload.to_numpy_bits(dw.out)) - plain).max() <= BF16_MAX_ABS
+    first = B.DeviceWorkload.to_numpy_bits(dw.out).tobytes()
+    dw.attention_shared()                               # again into the same workspace: same bits
+    torch.cuda.synchronize()
+    assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
+    dw.plan_shared(use_hint=False)                      # without the hint and the bounds: the page table's width rules
+    dw.out.zero_()
+    dw.attention_shared()
+    torch.cuda.synchronize()
+    _compare(wl, dw)
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
