@@ -207,21 +207,19 @@ def main():
         gbs = wl.kv_read_bytes() / (attn_ms * 1e-3) / 1e9
         log("workload %s: %.4f ms/step (attention %.4f ms, scatter %.4f ms), %.0f GB/s of K/V read"
             % (wl.name, ms, attn_ms, scat_ms, gbs))
-        shared = None
-        if True:
-            # the same batch through emm_decode_attn_shared with what the host knows of it: shared pages are
-            # read once per unit, and pieces are sized for the real amount of work, not for the longest context
-            plan = dw.plan_shared()
-            ms_s, attn_s, scat_s = time_workload(dw, args.steps, args.warmup, dw.attention_shared)
-            elt = 2 * wl.num_kv_heads * wl.head_dim * wl.elt_bytes          # K and V bytes per context token
-            saved = int(sum(int(l) * (int(n) - 1) for l, n in zip(plan["unit_shared_len"], plan["unit_num_reqs"]))) * elt
-            read = wl.kv_read_bytes() - saved
-            shared = {"num_units": plan["num_units"], "planned_tiles": plan["planned_tiles"], "ms_per_step": ms_s, "attention_ms": attn_s,
-                      "kv_bytes_read_per_step": read, "read_gbs": read / (attn_s * 1e-3) / 1e9,
-                      "frac_hbm_peak": read / (attn_s * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                      "speedup_over_unshared_attention": attn_ms / attn_s}
-            log("  planned (%d shared-prefix units, %d tiles): attention %.4f ms (%.2fx), %.0f GB/s of the %.0f MB it reads"
-                % (plan["num_units"], plan["planned_tiles"], attn_s, attn_ms / attn_s, shared["read_gbs"], read / 1e6))
+        # the same batch through emm_decode_attn_shared with what the host knows of it: shared pages are
+        # read once per unit, and pieces are sized for the real amount of work, not for the longest context
+        plan = dw.plan_shared()
+        ms_s, attn_s, scat_s = time_workload(dw, args.steps, args.warmup, dw.attention_shared)
+        elt = 2 * wl.num_kv_heads * wl.head_dim * wl.elt_bytes          # K and V bytes per context token
+        saved = int(sum(int(l) * (int(n) - 1) for l, n in zip(plan["unit_shared_len"], plan["unit_num_reqs"]))) * elt
+        read = wl.kv_read_bytes() - saved
+        shared = {"num_units": plan["num_units"], "planned_tiles": plan["planned_tiles"], "ms_per_step": ms_s, "attention_ms": attn_s,
+                  "kv_bytes_read_per_step": read, "read_gbs": read / (attn_s * 1e-3) / 1e9,
+                  "frac_hbm_peak": read / (attn_s * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                  "speedup_over_unshared_attention": attn_ms / attn_s}
+        log("  planned (%d shared-prefix units, %d tiles): attention %.4f ms (%.2fx), %.0f GB/s of the %.0f MB it reads"
+            % (plan["num_units"], plan["planned_tiles"], attn_s, attn_ms / attn_s, shared["read_gbs"], read / 1e6))
         print(json.dumps({
             "metric": "decode_attention_kv_read_gbs", "value": wl.kv_read_bytes() / (ms * 1e-3) / 1e9, "unit": "GB/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,

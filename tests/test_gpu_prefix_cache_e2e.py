@@ -22,6 +22,7 @@ H, HKV, D, PS = 8, 2, 128, 16
 NUM_PAGES, MAX_PAGES = 22, 24
 SCALE = 1.0 / np.sqrt(D)
 TOL_MAX, TOL_MEAN = 2e-2, 2e-3
+UNITS_SEEN = []
 
 
 def _bf16_round(x: np.ndarray) -> np.ndarray:
@@ -76,6 +77,21 @@ def _run_batch(torch, pools, rows, reqs, decode=False):
     (B.emm_decode_attn if decode else B.emm_prefill_attn)(batch, q_d, k_pool, v_pool, out, None, ws)
     torch.cuda.synchronize()
     o = out.to(torch.float32).cpu().numpy().astype(np.float64)
+    if decode:
+        # the same step with the pages that the cache made common to several requests read once per unit
+        plan = B.emm_shared_prefix_plan_host(batch, pt.cpu().numpy(), pl_d.cpu().numpy(), new_lens)
+        UNITS_SEEN.append(plan["num_units"])
+        arrays = {k: torch.from_numpy(np.ascontiguousarray(v if len(v) else np.zeros(1, np.int32))).to("cuda:0")
+                  for k, v in plan.items() if isinstance(v, np.ndarray)}
+        sp = B.make_shared_prefix(plan["num_units"], planned_tiles=plan["planned_tiles"],
+                                  max_own_tiles=plan["max_own_tiles"], max_unit_tiles=plan["max_unit_tiles"], **arrays)
+        ws2 = torch.empty(max(B.emm_decode_attn_shared_workspace_size(batch, sp), 16), dtype=torch.uint8, device="cuda:0")
+        out2 = torch.zeros_like(q_d)
+        B.emm_decode_attn_shared(batch, sp, q_d, k_pool, v_pool, out2, None, ws2)
+        torch.cuda.synchronize()
+        o2 = out2.to(torch.float32).cpu().numpy().astype(np.float64)
+        assert np.abs(o2 - o).max() <= TOL_MAX
+        o = o2                                           # the caller checks this one against the oracle
     return [o[cu[i]:cu[i + 1]] for i in range(len(reqs))]
 
 
@@ -140,6 +156,7 @@ def test_cached_prefixes_give_the_answers_of_full_prefill():
         for st in state:
             PC.emm_prefix_cache_release(cache, st[1])
     st = PC.emm_prefix_cache_get_stats(cache)
+    assert max(UNITS_SEEN) >= 1                      # requests of a wave that hit the same cached pages formed units
     assert hits > 0 and st["hit_tokens"] == hits
     assert st["evictions"] > 0                       # pages were reused for other content along the way
     assert st["live_requests"] == 0 and st["free_pages"] + st["cached_pages"] == NUM_PAGES
