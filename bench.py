@@ -159,6 +159,70 @@ def bench_prefix_cache(with_model: bool):
     print(json.dumps(result), flush=True)
 
 
+def bench_kv_migrate(torch, B, steps, warmup):
+    """Pack and unpack (with Adler-32 per page) the pages of one long video context and of a whole instance's
+    worth of requests: 16 KB per page in each pool (4 KV heads, bf16, one layer), scattered page ids.  Bytes moved = read +
+    write = 2 x the pages' bytes per call."""
+    import numpy as np
+    page_bytes, pool_pages = 4 * 16 * 128 * 2, 40000
+    k = torch.randint(-2 ** 15, 2 ** 15, (pool_pages, page_bytes // 2), dtype=torch.int16, device="cuda:0")
+    v = torch.randint(-2 ** 15, 2 ** 15, (pool_pages, page_bytes // 2), dtype=torch.int16, device="cuda:0")
+    k2, v2 = torch.zeros_like(k), torch.zeros_like(v)
+    rng = np.random.default_rng(5)
+    out = {}
+    for name, n in (("one_video_context_18432_tokens", 1152), ("64_contexts_of_8192_tokens", 32768)):
+        src = torch.from_numpy(rng.permutation(pool_pages)[:n].astype(np.int32)).to("cuda:0")
+        dst = torch.from_numpy(rng.permutation(pool_pages)[:n].astype(np.int32)).to("cuda:0")
+        staging = torch.empty(n * 2 * page_bytes, dtype=torch.uint8, device="cuda:0")
+        sums, sums2 = torch.zeros(n, dtype=torch.int32, device="cuda:0"), torch.zeros(n, dtype=torch.int32, device="cuda:0")
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        for i in range(-warmup, steps):
+            if i >= 0:
+                ev[i][0].record()
+            B.emm_kv_pages_pack(k, v, pool_pages, page_bytes, src, n, staging, sums)
+            if i >= 0:
+                ev[i][1].record()
+            B.emm_kv_pages_unpack(staging, dst, n, k2, v2, pool_pages, page_bytes, sums2, sums, bad)
+            if i >= 0:
+                ev[i][2].record()
+        torch.cuda.synchronize()
+        assert int(bad.item()) == 0 and torch.equal(sums, sums2)
+        assert torch.equal(k2[dst.long()], k[src.long()]) and torch.equal(v2[dst.long()], v[src.long()])
+        pack_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+        unpack_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+        moved = 2 * n * 2 * page_bytes
+        out[name] = {"pages": n, "bytes": n * 2 * page_bytes, "pack_ms": pack_ms, "unpack_ms": unpack_ms,
+                     "pack_gbs": moved / (pack_ms * 1e-3) / 1e9, "unpack_gbs": moved / (unpack_ms * 1e-3) / 1e9}
+        log("kv migrate %s: pack %.4f ms (%.0f GB/s read+write), unpack %.4f ms (%.0f GB/s)"
+            % (name, pack_ms, out[name]["pack_gbs"], unpack_ms, out[name]["unpack_gbs"]))
+    # for scale: a plain device-to-device copy of 1 GiB by the runtime
+    a1 = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    a2 = torch.empty_like(a1)
+    for _ in range(3):
+        a2.copy_(a1)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        a2.copy_(a1)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * (1 << 30) / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+    log("plain copy of 1 GiB: %.0f GB/s read+write" % copy_gbs)
+    big = out["64_contexts_of_8192_tokens"]
+    gbs = 2 * 2 * big["bytes"] / ((big["pack_ms"] + big["unpack_ms"]) * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "kv_page_migration_gbs", "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": big["pack_ms"] + big["unpack_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "pack + unpack of 32768 pages of 2 x 16 KB (64 contexts of 8192 tokens, 4 KV heads, bf16), "
+                               "Adler-32 per page on both sides", "parallelism": "single-gpu"},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "kv_pages_kernel<false> + kv_pages_kernel<true>"},
+        "cases": out, "plain_copy_gbs": copy_gbs,
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +238,8 @@ def main():
     ap.add_argument("--decode", default=None, metavar="NAME",
                     help="time one decode-step workload instead (one query token per request; HBM-bound): "
                          "decode_video_b8, decode_mixed_b32 or decode_b64_8k")
+    ap.add_argument("--kv-migrate", action="store_true",
+                    help="time the KV page migration primitive (pack and unpack with checksums) instead")
     ap.add_argument("--prefix-cache", action="store_true",
                     help="time the host-side prefix cache (no GPU work) on a synthetic request stream")
     args = ap.parse_args()
@@ -200,6 +266,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.kv_migrate:
+        return bench_kv_migrate(torch, B, args.steps, args.warmup)
     if args.decode is not None:
         wl = W.decode_config(args.decode)
         dw = B.DeviceWorkload(wl)

@@ -15,6 +15,7 @@
  *                     for encoder-decoder models                                  (Section 2.1)
  *   emm_decode_attn   the same attention for the decode step, one new token per request (Section 2.2)
  *   emm_decode_attn_shared  the decode step reading pages that several requests share once (Section 3.3)
+ *   emm_kv_pages_pack / emm_kv_pages_unpack  the two ends of a KV cache migration      (Appendix B.5)
  *
  * Conventions common to all calls
  *   - Every pointer marked "device" is memory of the current HIP device, owned by the caller; the
@@ -202,6 +203,28 @@ emm_status emm_shared_prefix_plan_host(const emm_batch *batch, const int32_t *ho
 emm_status emm_cross_attn(const emm_batch *batch, const void *q, const void *k_cache,
                           const void *v_cache, void *out, float *lse, void *workspace,
                           size_t workspace_bytes, void *hip_stream);
+
+/*
+ * KV page migration primitive (Appendix B.5: when an instance is scaled, a request's KV cache is copied to
+ * another GPU exactly and the copy is verified with checksums).  These two calls are the ends of such a
+ * move on one GPU each; the transport between them is not part of this library.
+ *   emm_kv_pages_pack    gathers pages page_ids[0..n-1] of both pools into `staging`: page i occupies bytes
+ *                        [i * 2 * page_bytes, (i+1) * 2 * page_bytes), the K page (all KV heads) first, then
+ *                        the V page; checksums[i] (optional) = Adler-32 (RFC 1950) of those bytes.
+ *   emm_kv_pages_unpack  scatters such a buffer into pages page_ids[0..n-1] of the destination pools, bit for
+ *                        bit, and takes the same checksums of what it received; with `expected` and
+ *                        `mismatches` given, *mismatches is incremented once per page whose checksum differs
+ *                        from expected[i] (the caller zeroes it beforehand).
+ * page_bytes is the size of one page in ONE pool (num_kv_heads * page_size * head_dim * element size), a
+ * multiple of 16 up to 1 MiB.  All pointers are device memory, 16-byte aligned (checksums, expected,
+ * mismatches: 4); page ids are distinct and inside the pool of num_pages pages.  n == 0 is a no-op.
+ */
+emm_status emm_kv_pages_pack(const void *k_cache, const void *v_cache, int32_t num_pages, int64_t page_bytes,
+                             const int32_t *page_ids, int32_t n, void *staging, uint32_t *checksums,
+                             void *hip_stream);
+emm_status emm_kv_pages_unpack(const void *staging, const int32_t *page_ids, int32_t n, void *k_cache,
+                               void *v_cache, int32_t num_pages, int64_t page_bytes, uint32_t *checksums,
+                               const uint32_t *expected, uint32_t *mismatches, void *hip_stream);
 
 /*
  * Host-side consistency check of a batch whose arrays are given as HOST copies (debug / tests).

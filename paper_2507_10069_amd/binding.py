@@ -21,6 +21,7 @@ EMM_F32, EMM_BF16 = 0, 1
 
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
            "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
+           "emm_kv_pages_pack", "emm_kv_pages_unpack",
            "emm_validate_batch_host", "emm_status_string", "emm_version"]
 
 
@@ -77,6 +78,10 @@ def load() -> ctypes.CDLL:
     lib.emm_decode_attn_shared.argtypes = [bp, ctypes.POINTER(emm_shared_prefix), vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.emm_shared_prefix_plan_host.restype = ctypes.c_int
     lib.emm_shared_prefix_plan_host.argtypes = [bp, i32p, i32p, i32p, ctypes.c_int32] + [i32p] * 5 + [ctypes.POINTER(emm_shared_prefix)]
+    lib.emm_kv_pages_pack.restype = ctypes.c_int
+    lib.emm_kv_pages_pack.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_int32, vp, vp, vp]
+    lib.emm_kv_pages_unpack.restype = ctypes.c_int
+    lib.emm_kv_pages_unpack.argtypes = [vp, vp, ctypes.c_int32, vp, vp, ctypes.c_int32, ctypes.c_int64, vp, vp, vp, vp]
     lib.emm_validate_batch_host.restype = ctypes.c_int
     lib.emm_validate_batch_host.argtypes = [bp, i32p, i32p, i32p, i32p, ctypes.c_int]
     lib.emm_status_string.restype = ctypes.c_char_p
@@ -193,6 +198,19 @@ def emm_shared_prefix_plan_host(batch: emm_batch, page_table: np.ndarray, prefix
     return {"num_units": U, "planned_tiles": int(sp.planned_tiles), "max_own_tiles": int(sp.max_own_tiles),
             "max_unit_tiles": int(sp.max_unit_tiles), "unit_first_req": outs[0][:U], "unit_num_reqs": outs[1][:U], "unit_shared_len": outs[2][:U],
             "req_unit": outs[3][:B_], "req_shared_len": outs[4][:B_]}
+
+
+def emm_kv_pages_pack(k_cache, v_cache, num_pages: int, page_bytes: int, page_ids, n: int, staging, checksums=None,
+                      stream=None) -> None:
+    _check(load().emm_kv_pages_pack(_ptr(k_cache), _ptr(v_cache), num_pages, page_bytes, _ptr(page_ids), n,
+                                    _ptr(staging), _ptr(checksums), _stream(stream)), "emm_kv_pages_pack")
+
+
+def emm_kv_pages_unpack(staging, page_ids, n: int, k_cache, v_cache, num_pages: int, page_bytes: int, checksums=None,
+                        expected=None, mismatches=None, stream=None) -> None:
+    _check(load().emm_kv_pages_unpack(_ptr(staging), _ptr(page_ids), n, _ptr(k_cache), _ptr(v_cache), num_pages,
+                                      page_bytes, _ptr(checksums), _ptr(expected), _ptr(mismatches), _stream(stream)),
+           "emm_kv_pages_unpack")
 
 
 def emm_validate_batch_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray,

@@ -5,6 +5,7 @@
 #include "emm_internal.h"
 
 #include <algorithm>
+#include <initializer_list>
 #include <cmath>
 #include <cstdint>
 #include <vector>
@@ -277,6 +278,46 @@ emm_status emm_shared_prefix_plan_host(const emm_batch* b, const int32_t* pt, co
     shared->max_own_tiles = static_cast<int32_t>(std::max<int64_t>(own_max, 1));
     shared->max_unit_tiles = static_cast<int32_t>(unit_max);
     return EMM_OK;
+}
+
+static emm_status check_pages_args(const void* k_cache, const void* v_cache, const void* staging,
+                                   const int32_t* page_ids, int32_t n, int32_t num_pages, int64_t page_bytes,
+                                   const void* c0, const void* c1, const void* c2)
+{
+    if (n < 0 || num_pages < 0 || page_bytes < 16 || page_bytes % 16 != 0 || page_bytes > (1 << 20))
+        return EMM_ERR_INVALID_ARG;
+    if (n == 0) return EMM_OK;
+    if (k_cache == nullptr || v_cache == nullptr || staging == nullptr || page_ids == nullptr) return EMM_ERR_NULL;
+    if (num_pages == 0) return EMM_ERR_INVALID_ARG;
+    if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(staging)) return EMM_ERR_INVALID_ARG;
+    for (const void* c : {c0, c1, c2})
+        if (c != nullptr && (reinterpret_cast<uintptr_t>(c) & 3u) != 0) return EMM_ERR_INVALID_ARG;
+    return EMM_OK;
+}
+
+emm_status emm_kv_pages_pack(const void* k_cache, const void* v_cache, int32_t num_pages, int64_t page_bytes,
+                             const int32_t* page_ids, int32_t n, void* staging, uint32_t* checksums, void* hip_stream)
+{
+    const emm_status st = check_pages_args(k_cache, v_cache, staging, page_ids, n, num_pages, page_bytes, checksums,
+                                           nullptr, nullptr);
+    if (st != EMM_OK || n == 0) return st;
+    const hipError_t err = emm::launch_kv_pages(false, const_cast<void*>(k_cache), const_cast<void*>(v_cache), staging,
+                                                page_ids, n, num_pages, page_bytes, checksums, nullptr, nullptr,
+                                                static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
+}
+
+emm_status emm_kv_pages_unpack(const void* staging, const int32_t* page_ids, int32_t n, void* k_cache, void* v_cache,
+                               int32_t num_pages, int64_t page_bytes, uint32_t* checksums, const uint32_t* expected,
+                               uint32_t* mismatches, void* hip_stream)
+{
+    const emm_status st = check_pages_args(k_cache, v_cache, staging, page_ids, n, num_pages, page_bytes, checksums,
+                                           expected, mismatches);
+    if (st != EMM_OK || n == 0) return st;
+    const hipError_t err = emm::launch_kv_pages(true, k_cache, v_cache, const_cast<void*>(staging), page_ids, n, num_pages,
+                                                page_bytes, checksums, expected, mismatches,
+                                                static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
 }
 
 emm_status emm_cross_attn(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,

@@ -56,4 +56,9 @@ hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream);
 size_t attn_bf16_decode_shared_workspace_bytes(const BatchView& b, const SharedPrefixView& sv);
 hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream);
 
+// KV page migration: pack (pools -> staging) or unpack (staging -> pools) n pages with a checksum per page
+hipError_t launch_kv_pages(bool unpack, void* k_cache, void* v_cache, void* staging, const int32_t* page_ids, int n,
+                           int num_pages, long long page_bytes, uint32_t* checksums, const uint32_t* expected,
+                           uint32_t* mismatches, hipStream_t stream);
+
 }  // namespace emm

@@ -223,3 +223,22 @@ def test_decode_shared_argument_checks():
     sp = B.make_shared_prefix(num_units=1)
     assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), ctypes.byref(sp), None) == B.EMM_ERR_NULL
     assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), None, ctypes.byref(n)) == B.EMM_ERR_NULL
+
+
+def test_kv_pages_argument_checks():
+    lib = B.load()
+    ok_ptr = ctypes.c_void_p(4096)                       # never dereferenced: n == 0 or the checks fail first
+    def pack(page_bytes=16384, n=0, k=ok_ptr, staging=ok_ptr, num_pages=8, sums=None):
+        return lib.emm_kv_pages_pack(k, ok_ptr, num_pages, page_bytes, ok_ptr, n, staging, sums, None)
+    assert pack() == B.EMM_OK                            # nothing to move
+    assert pack(page_bytes=100) == B.EMM_ERR_INVALID_ARG
+    assert pack(page_bytes=0) == B.EMM_ERR_INVALID_ARG
+    assert pack(page_bytes=(1 << 20) + 16) == B.EMM_ERR_INVALID_ARG
+    assert pack(n=-1) == B.EMM_ERR_INVALID_ARG
+    assert pack(n=1, k=None) == B.EMM_ERR_NULL
+    assert pack(n=1, staging=None) == B.EMM_ERR_NULL
+    assert pack(n=1, num_pages=0) == B.EMM_ERR_INVALID_ARG
+    assert pack(n=1, k=ctypes.c_void_p(4100)) == B.EMM_ERR_INVALID_ARG
+    assert pack(n=1, sums=ctypes.c_void_p(4098)) == B.EMM_ERR_INVALID_ARG
+    assert lib.emm_kv_pages_unpack(None, ok_ptr, 1, ok_ptr, ok_ptr, 8, 16384, None, None, None, None) == B.EMM_ERR_NULL
+    assert lib.emm_kv_pages_unpack(ok_ptr, ok_ptr, 0, ok_ptr, ok_ptr, 8, 16384, None, None, None, None) == B.EMM_OK

@@ -250,6 +250,67 @@ def test_decode_shared_prefix_parity(name, H, Hkv, ctx, new, group, shared, n_un
     _compare(wl, dw)
 
 
+def test_kv_page_migration_is_exact_and_checksummed():
+    """Appendix B.5 on one GPU: a request's pages are packed, checksummed, unpacked into other pages of another
+    pool; bytes and Adler-32 values must equal the reference's, a corrupted buffer must be reported, and decode
+    attention over the migrated pages must give the same bits as over the original ones."""
+    from oracle import kv_migrate_model as KM
+    print("case kv page migration", flush=True)
+    wl = W.build_workload("migrate", "causal", "bf16", 1500, num_q_heads=28, num_kv_heads=4, head_dim=128, page_size=16,
+                          prefix_lens=[3000, 37, 1200], new_lens=[1, 1, 1])
+    dw = _gpu_run(wl)                                   # scatter + decode on the source pools
+    src_out = B.DeviceWorkload.to_numpy_bits(dw.out).tobytes()
+    page_bytes = 4 * 16 * 128 * 2
+    kc, vc = B.DeviceWorkload.to_numpy_bits(dw.k_cache), B.DeviceWorkload.to_numpy_bits(dw.v_cache)
+    rng = np.random.default_rng(9)
+    dst_pages = wl.num_pages + 11
+    free = rng.permutation(dst_pages)
+    new_table = np.full_like(wl.page_table, -1)
+    kd = torch.full((dst_pages, 4, 16, 128), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    vd = torch.full_like(kd, -3.0)
+    kd_ref, vd_ref = B.DeviceWorkload.to_numpy_bits(kd).copy(), B.DeviceWorkload.to_numpy_bits(vd).copy()
+    taken = 0
+    for r in range(wl.num_reqs):                        # one request at a time, as a migration would go
+        n = -(-(int(wl.prefix_lens[r]) + 1) // 16)
+        src_ids = wl.page_table[r, :n].astype(np.int32)
+        dst_ids = free[taken:taken + n].astype(np.int32)
+        taken += n
+        new_table[r, :n] = dst_ids
+        ids_d, dst_d = torch.from_numpy(src_ids).to("cuda:0"), torch.from_numpy(dst_ids).to("cuda:0")
+        staging = torch.zeros(n * 2 * page_bytes, dtype=torch.uint8, device="cuda:0")
+        sums = torch.zeros(n, dtype=torch.int32, device="cuda:0")
+        B.emm_kv_pages_pack(dw.k_cache, dw.v_cache, wl.num_pages, page_bytes, ids_d, n, staging, sums)
+        ref_staging, ref_sums = KM.pack(kc, vc, src_ids)
+        assert staging.cpu().numpy().tobytes() == ref_staging.tobytes()
+        assert (sums.cpu().numpy().view(np.uint32) == ref_sums).all()
+        sums2 = torch.zeros_like(sums)
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        B.emm_kv_pages_unpack(staging, dst_d, n, kd, vd, dst_pages, page_bytes, sums2, sums, bad)
+        kd_ref, vd_ref, ref_sums2 = KM.unpack(ref_staging, dst_ids, kd_ref, vd_ref)
+        assert (sums2.cpu().numpy().view(np.uint32) == ref_sums2).all() and int(bad.item()) == 0
+        if r == 0:                                      # a bit flipped in transit is counted, once per damaged page
+            hurt = staging.clone()
+            hurt[5 * 2 * page_bytes + 123] ^= 4
+            hurt[(n - 1) * 2 * page_bytes] ^= 1
+            scratch_k, scratch_v = kd.clone(), vd.clone()
+            B.emm_kv_pages_unpack(hurt, dst_d, n, scratch_k, scratch_v, dst_pages, page_bytes, None, sums, bad)
+            assert int(bad.item()) == 2
+    torch.cuda.synchronize()
+    assert B.DeviceWorkload.to_numpy_bits(kd).tobytes() == kd_ref.tobytes()
+    assert B.DeviceWorkload.to_numpy_bits(vd).tobytes() == vd_ref.tobytes()
+    # the destination instance continues decoding: same query, migrated pages, other page ids -> same bits
+    pt_d = torch.from_numpy(new_table).to("cuda:0")
+    batch = B.make_batch(num_reqs=wl.num_reqs, num_q_heads=28, num_kv_heads=4, head_dim=128, page_size=16,
+                         num_pages=dst_pages, max_pages_per_req=wl.max_pages_per_req, total_new_tokens=3, max_new_len=1,
+                         dtype="bf16", softmax_scale=wl.softmax_scale, page_table=pt_d, prefix_lens=dw.prefix_lens,
+                         new_lens=dw.new_lens, cu_new_lens=dw.cu_new_lens)
+    out = torch.zeros_like(dw.out)
+    ws = torch.empty(B.emm_prefill_attn_workspace_size(batch), dtype=torch.uint8, device="cuda:0")
+    B.emm_decode_attn(batch, dw.q, kd, vd, out, None, ws)
+    torch.cuda.synchronize()
+    assert B.DeviceWorkload.to_numpy_bits(out).tobytes() == src_out
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
