@@ -288,6 +288,28 @@ def main():
                   "speedup_over_unshared_attention": attn_ms / attn_s}
         log("  planned (%d shared-prefix units, %d tiles): attention %.4f ms (%.2fx), %.0f GB/s of the %.0f MB it reads"
             % (plan["num_units"], plan["planned_tiles"], attn_s, attn_ms / attn_s, shared["read_gbs"], read / 1e6))
+        # the whole step (scatter + attention) as ONE call, emm_decode_step, without and with the units
+        # (both timed the same way here: K steps back to back between two events)
+        def two_calls(attention):
+            dw.scatter()
+            attention()
+        fused = {}
+        for key, fn in (("plain", lambda: dw.decode_step(False)), ("planned", lambda: dw.decode_step(True)),
+                        ("plain_two_calls", lambda: two_calls(dw.attention)),
+                        ("planned_two_calls", lambda: two_calls(dw.attention_shared))):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            fused[key] = max(e0.elapsed_time(e1), (time.perf_counter() - t0) * 1e3) / args.steps
+        log("  step as one call (emm_decode_step): %.4f ms plain (scatter + attention: %.4f), %.4f ms planned (%.4f)"
+            % (fused["plain"], fused["plain_two_calls"], fused["planned"], fused["planned_two_calls"]))
         print(json.dumps({
             "metric": "decode_attention_kv_read_gbs", "value": wl.kv_read_bytes() / (ms * 1e-3) / 1e9, "unit": "GB/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
@@ -298,7 +320,7 @@ def main():
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": gbs / HBM_PEAK_GBS, "traffic": None,
                          "kernel": "attn_bf16_decode_kernel + attn_bf16_decode_merge_kernel"},
-            "shared_prefix": shared,
+            "shared_prefix": shared, "fused_step_ms": fused,
         }), flush=True)
         return
 

@@ -15,6 +15,7 @@
  *                     for encoder-decoder models                                  (Section 2.1)
  *   emm_decode_attn   the same attention for the decode step, one new token per request (Section 2.2)
  *   emm_decode_attn_shared  the decode step reading pages that several requests share once (Section 3.3)
+ *   emm_decode_step   scatter + decode attention of one step in one launch               (Section 2.2)
  *   emm_kv_pages_pack / emm_kv_pages_unpack  the two ends of a KV cache migration      (Appendix B.5)
  *
  * Conventions common to all calls
@@ -165,8 +166,9 @@ typedef struct {
     const int32_t *req_shared_len;     /* device [B]                                                         */
 } emm_shared_prefix;
 
-/* Workspace bytes of emm_decode_attn_shared for this batch and the four scalar fields of `shared` (the values
- * the call itself will be given; num_units <= num_reqs / 2; the pointers are not looked at).
+/* Workspace bytes of emm_decode_attn_shared / emm_decode_step for this batch and the four scalar fields of
+ * `shared` (the values the call itself will be given; num_units <= num_reqs / 2; the pointers are not looked
+ * at; NULL = no units and no hints).
  * EMM_ERR_UNSUPPORTED unless the batch is EMM_BF16, head_dim 128, at most 16 query heads per KV head. */
 emm_status emm_decode_attn_shared_workspace_size(const emm_batch *batch, const emm_shared_prefix *shared,
                                                  size_t *bytes);
@@ -175,6 +177,19 @@ emm_status emm_decode_attn_shared_workspace_size(const emm_batch *batch, const e
 emm_status emm_decode_attn_shared(const emm_batch *batch, const emm_shared_prefix *shared, const void *q,
                                   const void *k_cache, const void *v_cache, void *out, float *lse,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One decode step in one call: emm_kv_scatter of the query tokens' K/V rows and emm_decode_attn (or, with
+ * units, emm_decode_attn_shared) fused, which saves a kernel launch per layer and step.  k_new / v_new
+ * [T][Hkv][d] hold the rows of the new tokens, which need NOT be in the pools beforehand: the attention
+ * kernel reads them from here and stores them in their slots (slot prefix_lens[r] of request r), so the pools
+ * are written.  `shared` may be NULL (no units, no hints).  Same results as the two separate calls, bit for
+ * bit.  Workspace: emm_decode_attn_shared_workspace_size with the same `shared`.  EMM_ERR_UNSUPPORTED unless
+ * the batch is EMM_BF16, head_dim 128, at most 16 query heads per KV head (use the two calls then).
+ */
+emm_status emm_decode_step(const emm_batch *batch, const emm_shared_prefix *shared, const void *q,
+                           const void *k_new, const void *v_new, void *k_cache, void *v_cache, void *out,
+                           float *lse, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Finds units in a batch given as HOST copies of its arrays: greedily, from each request on, the following

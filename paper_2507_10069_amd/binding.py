@@ -21,7 +21,7 @@ EMM_F32, EMM_BF16 = 0, 1
 
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
            "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
-           "emm_kv_pages_pack", "emm_kv_pages_unpack",
+           "emm_decode_step", "emm_kv_pages_pack", "emm_kv_pages_unpack",
            "emm_validate_batch_host", "emm_status_string", "emm_version"]
 
 
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.emm_decode_attn_shared.argtypes = [bp, ctypes.POINTER(emm_shared_prefix), vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.emm_shared_prefix_plan_host.restype = ctypes.c_int
     lib.emm_shared_prefix_plan_host.argtypes = [bp, i32p, i32p, i32p, ctypes.c_int32] + [i32p] * 5 + [ctypes.POINTER(emm_shared_prefix)]
+    lib.emm_decode_step.restype = ctypes.c_int
+    lib.emm_decode_step.argtypes = [bp, ctypes.POINTER(emm_shared_prefix)] + [vp] * 8 + [ctypes.c_size_t, vp]
     lib.emm_kv_pages_pack.restype = ctypes.c_int
     lib.emm_kv_pages_pack.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_int32, vp, vp, vp]
     lib.emm_kv_pages_unpack.restype = ctypes.c_int
@@ -182,6 +184,14 @@ def emm_decode_attn_shared(batch: emm_batch, shared: emm_shared_prefix, q, k_cac
                                          _stream(stream)), "emm_decode_attn_shared")
 
 
+def emm_decode_step(batch: emm_batch, shared: Optional[emm_shared_prefix], q, k_new, v_new, k_cache, v_cache, out, lse=None,
+                    workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    _check(load().emm_decode_step(ctypes.byref(batch), ctypes.byref(shared) if shared is not None else None, _ptr(q),
+                                  _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse),
+                                  _ptr(workspace), ws_bytes, _stream(stream)), "emm_decode_step")
+
+
 def emm_shared_prefix_plan_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray,
                                 new_lens: np.ndarray, min_shared_tokens: int = 32) -> dict:
     """Returns the units as host int32 arrays: unit_first_req, unit_num_reqs, unit_shared_len (length U),
@@ -281,6 +291,11 @@ class DeviceWorkload:
         self.shared_workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=self.device)
         self.shared_plan = plan
         return plan
+
+    def decode_step(self, shared: bool = False, stream=None) -> None:
+        """Scatter + decode attention in one call (emm_decode_step), with the planned units or without."""
+        emm_decode_step(self.batch, self.shared if shared else None, self.q, self.k_new, self.v_new, self.k_cache,
+                        self.v_cache, self.out, self.lse, self.shared_workspace if shared else self.workspace, stream)
 
     def attention_shared(self, stream=None) -> None:
         emm_decode_attn_shared(self.batch, self.shared, self.q, self.k_cache, self.v_cache, self.out, self.lse,

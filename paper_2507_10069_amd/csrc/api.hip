@@ -77,15 +77,18 @@ emm::SharedPrefixView shared_view_of(const emm_shared_prefix* sp)
 // sp: shared-prefix units of a decode batch, or nullptr
 emm_status attention(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache, void* out,
                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, int causal,
-                     const emm_shared_prefix* sp = nullptr)
+                     const emm_shared_prefix* sp = nullptr, const void* k_new = nullptr, const void* v_new = nullptr,
+                     bool fused = false)
 {
     emm_status st = check_scalars(b);
     if (st != EMM_OK) return st;
     st = check_supported(b);
     if (st != EMM_OK) return st;
+    static const emm_shared_prefix no_units = {};
     if (sp != nullptr) {
         if (sp->num_units == 0 && sp->planned_tiles == 0 && sp->max_own_tiles == 0) sp = nullptr;
     }
+    if (fused && sp == nullptr) sp = &no_units;              // the fused step goes through the same planner
     size_t need = 0;
     st = sp != nullptr ? emm_decode_attn_shared_workspace_size(b, sp, &need)
                        : emm_prefill_attn_workspace_size(b, &need);
@@ -97,6 +100,8 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     st = check_arrays(b);
     if (st != EMM_OK) return st;
     if (q == nullptr || k_cache == nullptr || v_cache == nullptr || out == nullptr) return EMM_ERR_NULL;
+    if (fused && (k_new == nullptr || v_new == nullptr)) return EMM_ERR_NULL;
+    if (fused && (!aligned16(k_new) || !aligned16(v_new))) return EMM_ERR_INVALID_ARG;
     if (need > 0 && workspace == nullptr) return EMM_ERR_NULL;
     if (workspace_bytes < need) return EMM_ERR_WORKSPACE;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
@@ -114,11 +119,14 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     args.lse = lse;
     args.causal = causal;
     args.workspace = need > 0 ? workspace : nullptr;
+    args.k_new = k_new;
+    args.v_new = v_new;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err;
     if (sp != nullptr) {
         const emm::SharedPrefixView sv = shared_view_of(sp);
-        err = emm::launch_attn_bf16_decode_shared(args, sv, stream);
+        err = fused ? emm::launch_attn_bf16_decode_step(args, sv, stream)
+                    : emm::launch_attn_bf16_decode_shared(args, sv, stream);
     } else if (b->dtype != EMM_BF16) err = emm::launch_attn_f32(args, stream);
     else if (emm::attn_bf16_decode_applies(args.b)) err = emm::launch_attn_bf16_decode(args, stream);
     else err = emm::launch_attn_bf16_d128(args, stream);
@@ -186,7 +194,8 @@ emm_status emm_decode_attn_shared_workspace_size(const emm_batch* b, const emm_s
     if (st != EMM_OK) return st;
     st = check_supported(b);
     if (st != EMM_OK) return st;
-    if (sp == nullptr) return EMM_ERR_NULL;
+    static const emm_shared_prefix no_units = {};
+    if (sp == nullptr) sp = &no_units;
     if (sp->num_units < 0 || sp->num_units > b->num_reqs / 2 || sp->planned_tiles < 0 || sp->max_own_tiles < 0 ||
         sp->max_unit_tiles < 0)
         return EMM_ERR_INVALID_ARG;
@@ -203,6 +212,15 @@ emm_status emm_decode_attn_shared(const emm_batch* b, const emm_shared_prefix* s
 {
     if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
     return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1, shared);
+}
+
+emm_status emm_decode_step(const emm_batch* b, const emm_shared_prefix* shared, const void* q, const void* k_new,
+                           const void* v_new, void* k_cache, void* v_cache, void* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* hip_stream)
+{
+    if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
+    return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1, shared, k_new, v_new,
+                     true);
 }
 
 emm_status emm_shared_prefix_plan_host(const emm_batch* b, const int32_t* pt, const int32_t* prefix,

@@ -25,6 +25,11 @@
 // 32 columns of the MFMA, while the requests' own workgroups start behind the shared part; the merge
 // kernel adds the records of both.  Built as a second instantiation (SHARED) so that the plain path pays
 // nothing for it.
+//
+// Fused step (FUSED instantiation, emm_decode_step): the query token's own K/V row need not be in the pool
+// beforehand.  The workgroup whose piece holds the token's slot copies the row from k_new / v_new into the
+// LDS tile once the tile has landed (into the swizzled places the loads would have put it) and stores it in
+// the pool when it is done, so a decode step is one launch less than scatter + attention.
 #include "attn_bf16_common.h"
 
 namespace emm {
@@ -74,9 +79,10 @@ __device__ __host__ inline size_t unit_records_offset(const DecodeShape& S)
     return (size_t)S.n_pairs * S.pieces_max * MAX_G * REC_FLOATS;
 }
 
-template <bool CAUSAL, bool SHARED>
+template <bool CAUSAL, bool SHARED, bool FUSED>
 __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, DecodeShape S, SharedPrefixView sv)
 {
+    static_assert(CAUSAL || !FUSED, "only a causal step has a new token to store");
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NSLOT * TILE_BYTES];   // K ring, then V ring
     constexpr int V_SM = NSLOT * TILE_BYTES;
 
@@ -172,6 +178,23 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
         }
     };
 
+    // FUSED: the tile of this piece that holds the query token's own slot (none in most workgroups); its K/V
+    // row comes from k_new / v_new, written by the waves that fetched the rows it replaces
+    const int new_tile = (FUSED && !unit_mode) ? (kv_len - 1) / BK - t_begin : -1;
+    const long long new_row_bytes = ((long long)b.cu_new_lens[r] * b.num_kv_heads + kvh) * (D * 2);
+    auto patch_new_row = [&](int i, int slot) {
+        if (FUSED && i == new_tile) {
+            const int kk = (kv_len - 1) % BK;                                  // key within the tile
+            const int rho = (kk & 16) + swap23(kk & 15);                       // LDS row of that key in the K tile
+            if (wave == (rho >> 3) && lane < 16)
+                *(uint4*)(smem + slot * TILE_BYTES + rho * 256 + ((lane ^ (rho & 15)) << 4)) =
+                    *(const uint4*)((const unsigned char*)a.k_new + new_row_bytes + lane * 16);
+            if (wave == (kk >> 3) && lane < 16)
+                *(uint4*)(smem + V_SM + slot * TILE_BYTES + kk * 256 + ((lane ^ ((kk & 3) << 2)) << 4)) =
+                    *(const uint4*)((const unsigned char*)a.v_new + new_row_bytes + lane * 16);
+        }
+    };
+
     const int k_rd0 = l32 * 256 + ((h32 ^ (l32 & 15)) << 4);
     const int v_rd0 = V_SM + (8 * h32 + ((lane & 15) >> 2)) * 256 +
                       ((4 * ((lane & 15) >> 2) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) + (lane & 1) * 8;
@@ -243,6 +266,7 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
         for (int i = 0; i < AHEAD; ++i) load_tile(i, i);     // past the piece's end: a clamped page, never read
         __builtin_amdgcn_s_waitcnt(0x0f70 | 4 * (AHEAD - 1));    // tile 0 has landed
         zero_v_tail(0, 0);
+        patch_new_row(0, 0);
         __syncthreads();
         int slot = 0;                                        // of tile i
         for (int i = 0; i < n_tiles; ++i) {
@@ -251,12 +275,23 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
             if ((i & (NW - 1)) == wave) compute_tile(i, slot);
             __builtin_amdgcn_s_waitcnt(0x0f70 | 4 * (AHEAD - 1));    // tile i+1 has landed
             zero_v_tail(i + 1, slot_next);
+            patch_new_row(i + 1, slot_next);
             __syncthreads();
             slot = slot_next;
         }
         __builtin_amdgcn_s_waitcnt(0x0f70);                  // the last fetches too, before LDS is reused
     }
     __syncthreads();                                         // every wave's fetches have landed, every read is done
+
+    if (FUSED && new_tile >= 0 && new_tile < n_tiles && wave == 0 && lane < 32) {
+        // the token's row goes to its slot in the pool (K by lanes 0..15, V by 16..31), for the steps to come
+        const int pos = kv_len - 1;
+        const int page = min(max(pt[pos >> 4], 0), b.num_pages - 1);
+        const long long dst = ((long long)page * b.num_kv_heads + kvh) * 4096 + (pos & 15) * 256 + (lane & 15) * 16;
+        const unsigned char* src = (const unsigned char*)(lane < 16 ? a.k_new : a.v_new) + new_row_bytes + (lane & 15) * 16;
+        unsigned char* pool = (unsigned char*)const_cast<void*>(lane < 16 ? a.k_cache : a.v_cache);
+        *(uint4*)(pool + dst) = *(const uint4*)src;
+    }
 
     // ---- merge 1: the waves' partial results, 16 rows at a time, through LDS (the rings are free now)
     float* __restrict__ red = (float*)smem;                  // [NW waves][16 rows][130]
@@ -443,7 +478,7 @@ DecodeShape decode_shape(const BatchView& b, const SharedPrefixView& sv = Shared
 
 bool attn_bf16_decode_applies(const BatchView& b)
 {
-    return b.max_new_len == 1 && b.num_q_heads / b.num_kv_heads <= MAX_G;
+    return b.max_new_len <= 1 && b.num_q_heads / b.num_kv_heads <= MAX_G;
 }
 
 size_t attn_bf16_decode_workspace_bytes(const BatchView& b)
@@ -460,7 +495,7 @@ size_t attn_bf16_decode_shared_workspace_bytes(const BatchView& b, const SharedP
 
 namespace {
 
-template <bool SHARED>
+template <bool SHARED, bool FUSED>
 hipError_t launch_decode(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream)
 {
     const BatchView& b = a.b;
@@ -470,9 +505,11 @@ hipError_t launch_decode(const AttnArgs& a, const SharedPrefixView& sv, hipStrea
     const long long grid = (long long)S.n_pairs * S.pieces_max + (long long)S.n_unit_pairs * S.pieces_unit;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)
-        hipLaunchKernelGGL((attn_bf16_decode_kernel<true, SHARED>), dim3((unsigned)grid), dim3(NT), 0, stream, a, S, sv);
+        hipLaunchKernelGGL((attn_bf16_decode_kernel<true, SHARED, FUSED>), dim3((unsigned)grid), dim3(NT), 0, stream, a, S, sv);
+    else if constexpr (!FUSED)
+        hipLaunchKernelGGL((attn_bf16_decode_kernel<false, SHARED, false>), dim3((unsigned)grid), dim3(NT), 0, stream, a, S, sv);
     else
-        hipLaunchKernelGGL((attn_bf16_decode_kernel<false, SHARED>), dim3((unsigned)grid), dim3(NT), 0, stream, a, S, sv);
+        return hipErrorInvalidValue;
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!SHARED && S.pieces_max == 1)) return err;   // one piece each: already written
     const int G = b.num_q_heads / b.num_kv_heads;
@@ -489,13 +526,18 @@ hipError_t launch_decode(const AttnArgs& a, const SharedPrefixView& sv, hipStrea
 
 hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream)
 {
-    return launch_decode<false>(a, SharedPrefixView{}, stream);
+    return launch_decode<false, false>(a, SharedPrefixView{}, stream);
 }
 
 hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream)
 {
     // without units only the bounds matter: the plain kernels, cut by the sharper plan
-    return sv.num_units > 0 ? launch_decode<true>(a, sv, stream) : launch_decode<false>(a, sv, stream);
+    return sv.num_units > 0 ? launch_decode<true, false>(a, sv, stream) : launch_decode<false, false>(a, sv, stream);
+}
+
+hipError_t launch_attn_bf16_decode_step(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream)
+{
+    return sv.num_units > 0 ? launch_decode<true, true>(a, sv, stream) : launch_decode<false, true>(a, sv, stream);
 }
 
 }  // namespace emm

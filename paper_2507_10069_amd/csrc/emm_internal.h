@@ -27,6 +27,8 @@ struct AttnArgs {
     float* lse;           // [T][H] or nullptr
     int32_t causal;       // 1: keys 0..P+j ; 0: keys 0..P-1
     void* workspace;      // scratch for the bf16 kernel's cut units, or nullptr
+    const void* k_new = nullptr;   // fused decode step only: the query tokens' own K/V rows [T][Hkv][d], which
+    const void* v_new = nullptr;   // the kernel reads from here and stores in the (then writable) pools
 };
 
 // Shared-prefix units of a decode batch (device arrays; see emm_shared_prefix in emm.h)
@@ -55,6 +57,8 @@ hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream);
 // the same with shared-prefix units (sv.num_units >= 1)
 size_t attn_bf16_decode_shared_workspace_bytes(const BatchView& b, const SharedPrefixView& sv);
 hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream);
+// the same, fused with the scatter of the query tokens' own K/V rows (a.k_new, a.v_new; pools writable; causal)
+hipError_t launch_attn_bf16_decode_step(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream);
 
 // KV page migration: pack (pools -> staging) or unpack (staging -> pools) n pages with a checksum per page
 hipError_t launch_kv_pages(bool unpack, void* k_cache, void* v_cache, void* staging, const int32_t* page_ids, int n,

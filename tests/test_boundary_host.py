@@ -222,7 +222,8 @@ def test_decode_shared_argument_checks():
                 num_units=1)[0] == B.EMM_ERR_UNSUPPORTED
     sp = B.make_shared_prefix(num_units=1)
     assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), ctypes.byref(sp), None) == B.EMM_ERR_NULL
-    assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), None, ctypes.byref(n)) == B.EMM_ERR_NULL
+    assert lib.emm_decode_attn_shared_workspace_size(ctypes.byref(b), None, ctypes.byref(n)) == B.EMM_OK   # no units, no hints
+    assert n.value == plain
 
 
 def test_kv_pages_argument_checks():
@@ -242,3 +243,18 @@ def test_kv_pages_argument_checks():
     assert pack(n=1, sums=ctypes.c_void_p(4098)) == B.EMM_ERR_INVALID_ARG
     assert lib.emm_kv_pages_unpack(None, ok_ptr, 1, ok_ptr, ok_ptr, 8, 16384, None, None, None, None) == B.EMM_ERR_NULL
     assert lib.emm_kv_pages_unpack(ok_ptr, ok_ptr, 0, ok_ptr, ok_ptr, 8, 16384, None, None, None, None) == B.EMM_OK
+
+
+def test_decode_step_argument_checks():
+    lib = B.load()
+    ok_ptr = ctypes.c_void_p(4096)
+    b = _batch(num_reqs=4, total_new_tokens=4, max_new_len=1)
+    def step(batch=b, k_new=ok_ptr, ws=ok_ptr, ws_bytes=1 << 30, shared=None):
+        return lib.emm_decode_step(ctypes.byref(batch), shared, ok_ptr, k_new, ok_ptr, ok_ptr, ok_ptr, ok_ptr, None, ws,
+                                   ws_bytes, None)
+    # device arrays of the batch are null here, so a call that passes the scalar checks stops at EMM_ERR_NULL
+    assert step() == B.EMM_ERR_NULL
+    assert step(batch=_batch(num_reqs=4, total_new_tokens=8, max_new_len=2)) == B.EMM_ERR_INVALID_ARG
+    assert step(batch=_batch(num_reqs=4, total_new_tokens=4, max_new_len=1, num_q_heads=34, num_kv_heads=2)) == B.EMM_ERR_UNSUPPORTED
+    assert step(batch=_batch(num_reqs=4, total_new_tokens=4, max_new_len=1, dtype="f32", head_dim=64)) == B.EMM_ERR_UNSUPPORTED
+    assert step(batch=_batch(num_reqs=0, total_new_tokens=0, max_new_len=0)) == B.EMM_OK

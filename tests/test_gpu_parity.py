@@ -250,6 +250,42 @@ def test_decode_shared_prefix_parity(name, H, Hkv, ctx, new, group, shared, n_un
     _compare(wl, dw)
 
 
+FUSED_CASES = [(c[0], c[2], c[3], c[4], c[5], None, None) for c in DECODE_CASES if c[1] == "causal" and c[0] != "decode_g17"] + \
+              [(c[0], c[1], c[2], c[3], c[4], c[5], c[6]) for c in SHARED_CASES]
+
+
+@pytest.mark.parametrize("name,H,Hkv,ctx,new,group,shared", FUSED_CASES)
+def test_fused_decode_step_equals_scatter_then_attention(name, H, Hkv, ctx, new, group, shared):
+    """emm_decode_step (the new tokens' K/V rows taken from k_new / v_new inside the attention kernel and stored
+    by it) against emm_kv_scatter followed by the attention call: same output bits, same pool bytes; with and
+    without shared-prefix units."""
+    print("case fused", name, flush=True)
+    def build():
+        return W.build_workload(name, "causal", "bf16", 1400 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                                page_size=16, prefix_lens=ctx, new_lens=new, share_group=group, shared_len=shared)
+    bits = B.DeviceWorkload.to_numpy_bits
+    ref = _gpu_run(build())                             # scatter, then plain decode attention
+    _compare(ref.wl, ref)
+    dw = B.DeviceWorkload(build())
+    dw.out.zero_()
+    dw.decode_step()
+    torch.cuda.synchronize()
+    assert bits(dw.out).tobytes() == bits(ref.out).tobytes()
+    assert bits(dw.k_cache).tobytes() == bits(ref.k_cache).tobytes() and bits(dw.v_cache).tobytes() == bits(ref.v_cache).tobytes()
+    assert np.array_equal(dw.lse.cpu().numpy(), ref.lse.cpu().numpy())
+    if group is not None:
+        ref.plan_shared()
+        ref.out.zero_()
+        ref.attention_shared()                          # pools already hold the new rows
+        dw2 = B.DeviceWorkload(build())
+        dw2.plan_shared()
+        dw2.out.zero_()
+        dw2.decode_step(shared=True)
+        torch.cuda.synchronize()
+        assert bits(dw2.out).tobytes() == bits(ref.out).tobytes()
+        assert bits(dw2.k_cache).tobytes() == bits(ref.k_cache).tobytes() and bits(dw2.v_cache).tobytes() == bits(ref.v_cache).tobytes()
+
+
 def test_kv_page_migration_is_exact_and_checksummed():
     """Appendix B.5 on one GPU: a request's pages are packed, checksummed, unpacked into other pages of another
     pool; bytes and Adler-32 values must equal the reference's, a corrupted buffer must be reported, and decode
