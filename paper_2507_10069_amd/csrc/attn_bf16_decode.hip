@@ -96,7 +96,7 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int n_items = unit_mode ? S.n_unit_pairs : S.n_pairs;
     const int pair = blk % n_items, piece = blk / n_items;                // unit mode: pair = (unit, KV head)
     const int kvh = pair % b.num_kv_heads;
-    const int unit = pair / b.num_kv_heads;
+    const int unit = pair / b.num_kv_heads;                               // own part: this is the request itself
     const int r = unit_mode ? sv.unit_first_req[unit] : unit;             // the request whose page table is read
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
