@@ -344,10 +344,13 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     }
 }
 
-// merge 2: one workgroup per (pair, query row), thread = (piece parity, channel); pairs with a single piece
-// were finished by the main kernel.  The weights of up to 256 pieces at a time go through LDS, so that the
-// loop over the records has nothing but independent loads in it.
-constexpr int MERGE_THREADS = 2 * D;
+// merge 2: one workgroup per (pair, query row), thread = (piece number mod 8, channel); pairs with a single
+// piece were finished by the main kernel.  Few workgroups, so what counts is the length of the chain of
+// memory round trips: every piece's (m, l) is loaded once, by its own thread, the weights of a chunk of pieces
+// go through LDS, and the loop over the records has nothing but independent loads in it.  GROUPS threads share
+// a channel: 8 when a row has many pieces (a single long context: 6.8 -> 4.8 us for 129 pieces), 2 when it has
+// few (a big batch, where 1024-thread workgroups would only crowd the chip).
+constexpr int MANY_PIECES = 48;
 
 __device__ inline float wave_max64(float x)
 {
@@ -362,10 +365,11 @@ __device__ inline float wave_sum64(float x)
     return x;
 }
 
-template <bool CAUSAL, bool SHARED>
-__global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(AttnArgs a, DecodeShape S, SharedPrefixView sv)
+template <bool CAUSAL, bool SHARED, int MERGE_GROUPS>
+__global__ __launch_bounds__(MERGE_GROUPS * D) void attn_bf16_decode_merge_kernel(AttnArgs a, DecodeShape S, SharedPrefixView sv)
 {
-    __shared__ float w_s[MERGE_THREADS], part_s[MERGE_THREADS / 64], acc_s[D];
+    constexpr int MERGE_THREADS = MERGE_GROUPS * D;
+    __shared__ float w_s[MERGE_THREADS], part_s[MERGE_THREADS / 64], acc_s[MERGE_GROUPS][D];
     const BatchView& b = a.b;
     const int G = b.num_q_heads / b.num_kv_heads;
     const int pair = blockIdx.x / G, row = blockIdx.x % G;
@@ -386,43 +390,61 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_bf16_decode_merge_kernel(A
     }
     const int n_pieces = n_own + n_unit;
     const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
-    const int tid = threadIdx.x, ch = tid % D, half = tid / D, wave = tid >> 6;
+    const int tid = threadIdx.x, ch = tid % D, grp = tid / D, wave = tid >> 6;
     const float* __restrict__ rec_own =
         (const float*)a.workspace + ((size_t)pair * S.pieces_max * MAX_G + row) * REC_FLOATS;
     auto record = [&](int j) -> const float* {               // this row in record j
         return j < n_own ? rec_own + (size_t)j * (MAX_G * REC_FLOATS) : rec_unit + (size_t)(j - n_own) * (MAX_ROWS * REC_FLOATS);   // consecutive pieces of the unit
     };
 
-    // the maximum over all pieces (every piece of a context that needs several has a visible key)
-    float m_all = -INFINITY;
-    for (int j = tid; j < n_pieces; j += MERGE_THREADS) m_all = fmaxf(m_all, record(j)[D]);
+    // the maximum over all pieces (every piece of a context that needs several has a visible key); the (m, l)
+    // of piece `tid` stay in registers for the weights below
+    float m_mine = -INFINITY, l_mine = 0.f;
+    if (tid < n_pieces) {
+        const float* src = record(tid);
+        m_mine = src[D];
+        l_mine = src[D + 1];
+    }
+    float m_all = m_mine;
+    for (int j = tid + MERGE_THREADS; j < n_pieces; j += MERGE_THREADS) m_all = fmaxf(m_all, record(j)[D]);
     m_all = wave_max64(m_all);
     if ((tid & 63) == 0) part_s[wave] = m_all;
     __syncthreads();
-    m_all = fmaxf(fmaxf(part_s[0], part_s[1]), fmaxf(part_s[2], part_s[3]));
+    m_all = part_s[0];
+#pragma unroll
+    for (int i = 1; i < MERGE_THREADS / 64; ++i) m_all = fmaxf(m_all, part_s[i]);
 
     float acc = 0.f, l_tot = 0.f;
     for (int c0 = 0; c0 < n_pieces; c0 += MERGE_THREADS) {
         __syncthreads();                                     // the weights of the chunk before have been used
         if (c0 + tid < n_pieces) {
-            const float* src = record(c0 + tid);
-            const float wgt = __builtin_amdgcn_exp2f((src[D] - m_all) * c_log2);
+            float m_j = m_mine, l_j = l_mine;
+            if (c0 > 0) {
+                const float* src = record(c0 + tid);
+                m_j = src[D];
+                l_j = src[D + 1];
+            }
+            const float wgt = __builtin_amdgcn_exp2f((m_j - m_all) * c_log2);
             w_s[tid] = wgt;
-            l_tot += wgt * src[D + 1];
+            l_tot += wgt * l_j;
         }
         __syncthreads();
         const int n = min(MERGE_THREADS, n_pieces - c0);
 #pragma unroll 8
-        for (int j = half; j < n; j += 2) acc += w_s[j] * record(c0 + j)[ch];
+        for (int j = grp; j < n; j += MERGE_GROUPS) acc += w_s[j] * record(c0 + j)[ch];
     }
     l_tot = wave_sum64(l_tot);
     __syncthreads();                                         // part_s is read above
     if ((tid & 63) == 0) part_s[wave] = l_tot;
-    if (half == 1) acc_s[ch] = acc;
+    acc_s[grp][ch] = acc;
     __syncthreads();
-    if (half == 0) {
-        acc += acc_s[ch];
-        l_tot = (part_s[0] + part_s[1]) + (part_s[2] + part_s[3]);
+    if (grp == 0) {
+        acc = 0.f;
+        l_tot = 0.f;
+#pragma unroll
+        for (int g = 0; g < MERGE_GROUPS; ++g) acc += acc_s[g][ch];
+#pragma unroll
+        for (int i = 0; i < MERGE_THREADS / 64; ++i) l_tot += part_s[i];
         const long long q_row = b.cu_new_lens[r];
         const int head = kvh * G + row;
         ((__bf16*)a.out)[(q_row * b.num_q_heads + head) * D + ch] = (__bf16)(l_tot > 0.f ? acc / l_tot : 0.f);
@@ -513,12 +535,16 @@ hipError_t launch_decode(const AttnArgs& a, const SharedPrefixView& sv, hipStrea
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || (!SHARED && S.pieces_max == 1)) return err;   // one piece each: already written
     const int G = b.num_q_heads / b.num_kv_heads;
-    if (a.causal)
-        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<true, SHARED>), dim3((unsigned)(S.n_pairs * G)),
-                           dim3(MERGE_THREADS), 0, stream, a, S, sv);
+    const dim3 mgrid((unsigned)(S.n_pairs * G));
+    const bool many = S.pieces_max + (SHARED ? S.pieces_unit : 0) > MANY_PIECES;
+    if (a.causal && many)
+        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<true, SHARED, 8>), mgrid, dim3(8 * D), 0, stream, a, S, sv);
+    else if (a.causal)
+        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<true, SHARED, 2>), mgrid, dim3(2 * D), 0, stream, a, S, sv);
+    else if (many)
+        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<false, SHARED, 8>), mgrid, dim3(8 * D), 0, stream, a, S, sv);
     else
-        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<false, SHARED>), dim3((unsigned)(S.n_pairs * G)),
-                           dim3(MERGE_THREADS), 0, stream, a, S, sv);
+        hipLaunchKernelGGL((attn_bf16_decode_merge_kernel<false, SHARED, 2>), mgrid, dim3(2 * D), 0, stream, a, S, sv);
     return hipGetLastError();
 }
 

@@ -307,6 +307,7 @@ def decode_config(name: str, shrink: int = 1) -> Workload:
       decode_video_b8   8 requests with the video context of config 3 (16384 + 2048 tokens), 28/4 heads
       decode_mixed_b32  the 32 requests of config 4 after their prefill (context = prefix + new), 32/8 heads
       decode_b64_8k     64 requests of 8192 tokens, 28/4 heads
+      decode_b1_16k, decode_b1_128k   a single request (latency regime), 28/4 heads
     and two with shared prefix pages (requests about the same video / the same system prompt and image):
       decode_shared_video_b8   as decode_video_b8, the 16384 video tokens in pages common to all 8 requests
       decode_shared_video_b32  8 videos with 4 requests each (402 MB of distinct K/V: more than the caches hold)
@@ -320,6 +321,10 @@ def decode_config(name: str, shrink: int = 1) -> Workload:
         ctx, H, Hkv, seed = [int(p) + int(n) for p, n in zip(c4.prefix_lens, c4.new_lens)], 32, 8, 2002
     elif name == "decode_b64_8k":
         ctx, H, Hkv, seed = [_s(8192, shrink)] * 64, 28, 4, 2003
+    elif name == "decode_b1_16k":
+        ctx, H, Hkv, seed = [_s(16384, shrink)], 28, 4, 2007
+    elif name == "decode_b1_128k":
+        ctx, H, Hkv, seed = [_s(131072, shrink)], 28, 4, 2008
     elif name == "decode_shared_video_b8":
         ctx, H, Hkv, seed = [_s(16384 + 2048, shrink)] * 8, 28, 4, 2004
         share_group, shared_len = [0] * 8, [_s(16384, shrink)] * 8
@@ -339,7 +344,7 @@ def decode_config(name: str, shrink: int = 1) -> Workload:
                           shared_len=shared_len, spare_pages=8)
 
 
-DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k")
+DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k", "decode_b1_16k", "decode_b1_128k")
 DECODE_SHARED_CONFIGS = ("decode_shared_video_b8", "decode_shared_video_b32", "decode_shared_image_b32")
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
