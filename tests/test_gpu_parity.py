@@ -286,6 +286,55 @@ def test_fused_decode_step_equals_scatter_then_attention(name, H, Hkv, ctx, new,
         assert bits(dw2.k_cache).tobytes() == bits(ref.k_cache).tobytes() and bits(dw2.v_cache).tobytes() == bits(ref.v_cache).tobytes()
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_decode_batches(seed):
+    """Random decode batches (head groupings, batch sizes, ragged contexts, runs of requests that share pages,
+    requests without a token): the plain path, the path with units, and emm_decode_step for both, each against
+    the oracle or, bit for bit, against its two-call counterpart."""
+    rng = np.random.default_rng(5000 + seed)
+    H, Hkv = [(8, 8), (28, 4), (32, 8), (16, 1), (12, 4), (6, 2)][int(rng.integers(6))]
+    n_req = int(rng.integers(1, 21))
+    ctx, new, group, shared = [], [], [], []
+    g = 0
+    while len(ctx) < n_req:
+        run = int(min(rng.integers(1, 7), n_req - len(ctx)))           # a run of requests with common leading pages
+        common = int(rng.choice([0, 0, 17, 32, 100, 512, 1500]))
+        for _ in range(run):
+            own = int(rng.choice([0, 1, 15, 31, 33, 200, 900, 2500]))
+            ctx.append(common + own)
+            new.append(0 if rng.random() < 0.1 else 1)
+            group.append(g)
+            shared.append(common)
+        g += 1
+    print("case random decode", seed, (H, Hkv), ctx, new, flush=True)
+    bits = B.DeviceWorkload.to_numpy_bits
+
+    def build():
+        return W.build_workload("rnd_decode", "causal", "bf16", 5100 + seed, num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                                page_size=16, prefix_lens=ctx, new_lens=new, share_group=group, shared_len=shared)
+    if sum(new) == 0:
+        new[0] = 1
+    ref = _gpu_run(build())
+    _compare(ref.wl, ref)
+    plain_out = bits(ref.out).copy()
+    plan = ref.plan_shared()
+    print("   units:", plan["num_units"], plan["unit_num_reqs"].tolist(), plan["unit_shared_len"].tolist(), flush=True)
+    ref.out.zero_()
+    ref.attention_shared()
+    torch.cuda.synchronize()
+    _compare(ref.wl, ref)
+    shared_out = bits(ref.out).copy()
+    for use_units, want in ((False, plain_out), (True, shared_out)):
+        dw = B.DeviceWorkload(build())
+        dw.plan_shared()
+        dw.out.zero_()
+        dw.decode_step(use_units)
+        torch.cuda.synchronize()
+        assert bits(dw.out).tobytes() == want.tobytes(), use_units
+        assert bits(dw.k_cache).tobytes() == bits(ref.k_cache).tobytes()
+        assert bits(dw.v_cache).tobytes() == bits(ref.v_cache).tobytes()
+
+
 def test_kv_page_migration_is_exact_and_checksummed():
     """Appendix B.5 on one GPU: a request's pages are packed, checksummed, unpacked into other pages of another
     pool; bytes and Adler-32 values must equal the reference's, a corrupted buffer must be reported, and decode
