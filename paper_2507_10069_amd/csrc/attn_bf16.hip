@@ -115,6 +115,7 @@ struct UnitPlan {
     int pair, tile;         // pair < 0: this workgroup has nothing to do
     int parts, part;        // the unit's key tiles are cut into `parts` ranges; this workgroup does range `part`
     int slot;               // tail slot of the unit within its XCD (meaningful when parts > 1)
+    bool rows_only;         // parts == 2 stands for a halving along the rows only (never a cut along the keys)
 };
 
 __host__ __device__ inline int split_factor_of(int rem)  // pieces per tail unit when rem units are left over
@@ -124,8 +125,11 @@ __host__ __device__ inline int split_factor_of(int rem)  // pieces per tail unit
     if (rem == 0 || rem > 12) return 1;
     return rem > 8 ? 2 : 4;
 }
-__device__ inline int split_factor(int rem) { return split_factor_of(rem); }
-inline int host_split_factor(int rem) { return split_factor_of(rem); }
+// 13 .. 16 leftover units are not cut along the keys (see above) but still halved along their rows: the 26 .. 32
+// halves fill the XCD's last round, cost nothing to merge, and each finishes in about 60 % of a unit's time
+__host__ __device__ inline bool rows_only_of(int rem) { return rem > 12 && rem <= CU_PER_XCD / 2; }
+__device__ inline int split_factor(int rem) { return rows_only_of(rem) ? 2 : split_factor_of(rem); }
+inline int host_split_factor(int rem) { return rows_only_of(rem) ? 2 : split_factor_of(rem); }
 
 // row tiles (units) of sub-pair sp
 __host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int sp)
@@ -157,7 +161,7 @@ __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31
 __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd)
 {
     UnitPlan u;
-    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0;
+    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false;
     const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
     const bool regular = in_xcd < n_regular;
     const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
@@ -183,7 +187,8 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
     const int rem = total % CU_PER_XCD;
     const int parts = split_factor(rem);
-    if (parts == 1) return u;                            // regular: whole unit; extra: nothing to do (pair < 0)
+    if (parts == 1) return u;
+    u.rows_only = rows_only_of(rem);                            // regular: whole unit; extra: nothing to do (pair < 0)
     const int first_tail = total - rem;
     if (regular) {
         const int before_mine = __builtin_amdgcn_readfirstlane(wave_sum32(pi < my_pi ? cnt : 0));
@@ -254,10 +259,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = CAUSAL ? P + last_row / G + 1 : P;    // keys this row tile can see
     const int n_tiles_unit = (kv_len + BC - 1) / BC;
-    // a unit that cannot be cut is done whole by its regular workgroup
-    if (plan.parts > 1 && !cuttable(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1)) {
-        if (plan.part > 0) return;
+    // A tail unit that cannot be cut along the keys (too short) is halved along its ROWS instead: waves 0-3 of
+    // the row tile work in the regular workgroup, waves 4-7 in the workgroup of piece 1, the other four only
+    // fetch.  Rows are independent, so nothing has to be merged, and with one working wave per SIMD a tile
+    // takes about 60 % of the time.  (With at most half a tile of rows there is nothing to halve.)
+    int row_half = -1;                                       // -1: all eight waves work on their rows
+    if (plan.parts > 1 && (plan.rows_only || !cuttable(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1))) {
+        const bool halve = n_rows - row0 > BR / 2;
+        if (plan.part > (halve ? 1 : 0)) return;
+        if (halve) row_half = plan.part;
         plan.parts = 1;
+        plan.part = 0;
     }
     // this workgroup's key tiles: t_begin .. t_begin + n_tiles - 1
     const int t_begin = plan.part * n_tiles_unit / plan.parts;
@@ -269,6 +281,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int l32 = lane & 31, h32 = lane >> 5;
 
     const int wrow0 = row0 + wave * 32;
+    // a wave without rows of its own (past the pair's last row, or the other half of a halved unit) computes nothing
+    const bool active = wrow0 < n_rows && (row_half < 0 || (wave >> 2) == row_half);
     const int my_row = wrow0 + l32;
     const int row_c = min(my_row, n_rows - 1);
     const int tok = row_c / G;                               // new-token index of this lane's row
@@ -466,6 +480,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0): this wave's rows have landed
         zero_v_tail(t_begin, 0);
         __syncthreads();
+        if (!active) {
+            // keep fetching this wave's share of every tile and meet the others at the barriers: the same
+            // loads, waits and barriers as an iteration of the main loop below, and nothing else
+            for (int i = t_begin; i + 1 < t_begin + n_tiles; ++i) {
+                const int R = (i - t_begin) & 3;
+                if (i + 3 - pg_base >= 64) refill_pages(i + 2);
+                load_k(i + 3, (R + 3) & 3);
+                load_v(i + 2, (R + 2) & 3);
+                __builtin_amdgcn_s_waitcnt(0x0f74);          // vmcnt(4)
+                if (i + 1 >= n_clear) zero_v_tail(i + 1, (R + 1) & 3);
+                __syncthreads();
+            }
+            return;
+        }
 
         f32x16 sc[2][2];                                     // scores of tile i live in sc[i & 1]
 
@@ -728,7 +756,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int P = b.prefix_lens[r];
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = a.causal ? P + last_row / G + 1 : P;
-    if (!cuttable((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1)) return;   // done whole
+    if (plan.rows_only || !cuttable((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1)) return;   // not cut along the keys
 
     const int tid = threadIdx.x;
     const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
