@@ -125,6 +125,13 @@ CUT_CASES = [
                                                                     # a last piece that would start on the diagonal
     ("cut_short", "causal", 28, 4, [1056], [300]),                  # 9 units per XCD, too short to cut
     ("cut_gqa1", "causal", 8, 8, [4100], [300]),                    # one head per group: 256 tokens per row tile
+    # units too short to cut along the keys are halved along their rows (two workgroups of four working waves)
+    ("halve_one", "causal", 28, 4, [700], [36]),                    # 252 rows: one unit per head, halved
+    ("halve_small", "causal", 28, 4, [700, 50], [18, 19]),          # 126 and 133 rows: nothing to halve / halved
+    ("halve_cross", "cross", 32, 8, [900, 333], [60, 61]),          # 240 and 244 rows, no mask
+    ("halve_14", "causal", 56, 8, [100], [512]),                    # 14 units per XCD: rows only, short context
+    ("halve_14_long", "causal", 56, 8, [9000], [512]),              # 14 units per XCD, long context: still rows only
+    ("halve_ragged", "causal", 28, 4, [300, 1056, 0, 77], [100, 37, 150, 3]),   # last row tiles of 188, 3, 26, 21 rows
 ]
 
 
