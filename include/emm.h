@@ -178,6 +178,15 @@ emm_status emm_decode_attn_shared(const emm_batch *batch, const emm_shared_prefi
                                   const void *k_cache, const void *v_cache, void *out, float *lse,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same for the cross-attention layers of an encoder-decoder model in the decode step (Section 2.1): one
+ * text query per request over cached image K/V, unmasked, requests that show the same image sharing its pages.
+ * Units as above with "prefix_lens" read as the number of cached image tokens; a request whose tokens are all
+ * shared has no part of its own.  emm_shared_prefix_plan_host serves here too (its hint and bounds then
+ * overestimate by at most one tile per request, which is harmless). */
+emm_status emm_cross_attn_shared(const emm_batch *batch, const emm_shared_prefix *shared, const void *q,
+                                 const void *k_cache, const void *v_cache, void *out, float *lse,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /*
  * One decode step in one call: emm_kv_scatter of the query tokens' K/V rows and emm_decode_attn (or, with
  * units, emm_decode_attn_shared) fused, which saves a kernel launch per layer and step.  k_new / v_new

@@ -21,7 +21,7 @@ EMM_F32, EMM_BF16 = 0, 1
 
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
            "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
-           "emm_decode_step", "emm_kv_pages_pack", "emm_kv_pages_unpack",
+           "emm_cross_attn_shared", "emm_decode_step", "emm_kv_pages_pack", "emm_kv_pages_unpack",
            "emm_validate_batch_host", "emm_status_string", "emm_version"]
 
 
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.emm_decode_attn_shared.argtypes = [bp, ctypes.POINTER(emm_shared_prefix), vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.emm_shared_prefix_plan_host.restype = ctypes.c_int
     lib.emm_shared_prefix_plan_host.argtypes = [bp, i32p, i32p, i32p, ctypes.c_int32] + [i32p] * 5 + [ctypes.POINTER(emm_shared_prefix)]
+    lib.emm_cross_attn_shared.restype = ctypes.c_int
+    lib.emm_cross_attn_shared.argtypes = lib.emm_decode_attn_shared.argtypes
     lib.emm_decode_step.restype = ctypes.c_int
     lib.emm_decode_step.argtypes = [bp, ctypes.POINTER(emm_shared_prefix)] + [vp] * 8 + [ctypes.c_size_t, vp]
     lib.emm_kv_pages_pack.restype = ctypes.c_int
@@ -182,6 +184,14 @@ def emm_decode_attn_shared(batch: emm_batch, shared: emm_shared_prefix, q, k_cac
     _check(load().emm_decode_attn_shared(ctypes.byref(batch), ctypes.byref(shared), _ptr(q), _ptr(k_cache),
                                          _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
                                          _stream(stream)), "emm_decode_attn_shared")
+
+
+def emm_cross_attn_shared(batch: emm_batch, shared: emm_shared_prefix, q, k_cache, v_cache, out, lse=None,
+                          workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    _check(load().emm_cross_attn_shared(ctypes.byref(batch), ctypes.byref(shared), _ptr(q), _ptr(k_cache),
+                                        _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
+                                        _stream(stream)), "emm_cross_attn_shared")
 
 
 def emm_decode_step(batch: emm_batch, shared: Optional[emm_shared_prefix], q, k_new, v_new, k_cache, v_cache, out, lse=None,
@@ -298,7 +308,8 @@ class DeviceWorkload:
                         self.v_cache, self.out, self.lse, self.shared_workspace if shared else self.workspace, stream)
 
     def attention_shared(self, stream=None) -> None:
-        emm_decode_attn_shared(self.batch, self.shared, self.q, self.k_cache, self.v_cache, self.out, self.lse,
+        fn = emm_decode_attn_shared if self.wl.kind == "causal" else emm_cross_attn_shared
+        fn(self.batch, self.shared, self.q, self.k_cache, self.v_cache, self.out, self.lse,
                                self.shared_workspace, stream)
 
     def step(self, stream=None) -> None:

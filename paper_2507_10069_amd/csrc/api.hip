@@ -214,6 +214,14 @@ emm_status emm_decode_attn_shared(const emm_batch* b, const emm_shared_prefix* s
     return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1, shared);
 }
 
+emm_status emm_cross_attn_shared(const emm_batch* b, const emm_shared_prefix* shared, const void* q,
+                                 const void* k_cache, const void* v_cache, void* out, float* lse, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream)
+{
+    if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
+    return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 0, shared);
+}
+
 emm_status emm_decode_step(const emm_batch* b, const emm_shared_prefix* shared, const void* q, const void* k_new,
                            const void* v_new, void* k_cache, void* v_cache, void* out, float* lse, void* workspace,
                            size_t workspace_bytes, void* hip_stream)

@@ -227,6 +227,32 @@ SHARED_CASES = [
 ]
 
 
+@pytest.mark.parametrize("name,H,Hkv,ctx,new,group,shared", [
+    ("xshared_same_image", 32, 8, [6404] * 6, [1] * 6, [0] * 6, [6404] * 6),           # all tokens shared: 6400 by the unit, 4 own
+    ("xshared_exact", 32, 8, [1600] * 3, [1, 1, 1], [0] * 3, [1600] * 3),               # a multiple of 32: no own part at all
+    ("xshared_mixed", 28, 4, [1601, 1601, 500, 3202, 3202, 3202], [1] * 6, [0, 0, 1, 2, 2, 2], [1601, 1601, 0, 3202, 3202, 3202]),
+    ("xshared_holes", 32, 8, [800, 800, 0, 800], [1, 1, 1, 0], [0, 0, 1, 0], [800, 800, 0, 800]),    # nothing cached; no query
+])
+def test_cross_decode_shared_prefix_parity(name, H, Hkv, ctx, new, group, shared):
+    """Decode step of a cross-attention layer (one text query per request over cached image K/V, unmasked) with the
+    image pages of requests that show the same image read once per unit."""
+    print("case", name, flush=True)
+    wl = W.build_workload(name, "cross", "bf16", 1600 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=ctx, new_lens=new, share_group=group, shared_len=shared)
+    dw = _gpu_run(wl)
+    _compare(wl, dw)
+    plain = as_f64(B.DeviceWorkload.to_numpy_bits(dw.out))
+    plan = dw.plan_shared()
+    print("   units:", plan["num_units"], plan["unit_num_reqs"].tolist(), plan["unit_shared_len"].tolist(), flush=True)
+    assert plan["num_units"] >= 1
+    dw.out.zero_()
+    dw.lse.zero_()
+    dw.attention_shared()
+    torch.cuda.synchronize()
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+    assert np.abs(as_f64(B.DeviceWorkload.to_numpy_bits(dw.out)) - plain).max() <= BF16_MAX_ABS
+
+
 @pytest.mark.parametrize("name,H,Hkv,ctx,new,group,shared,n_units", SHARED_CASES)
 def test_decode_shared_prefix_parity(name, H, Hkv, ctx, new, group, shared, n_units):
     """emm_decode_attn_shared with the units found by emm_shared_prefix_plan_host, against the oracle (which
