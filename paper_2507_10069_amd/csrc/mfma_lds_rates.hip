@@ -1,7 +1,7 @@
 // Standalone microbenchmark (not part of libemm.so): sustained v_mfma_f32_32x32x16_bf16 rate on gfx950
 // when the matrix pipe is fed like the attention kernel feeds it -- two waves per SIMD, operands with
 // realistic bit patterns, a few VALU instructions and LDS operand reads per MFMA.  It answers what the
-// attention kernel can at best reach, and is the source of the ceilings quoted in the design doc.
+// attention kernel can at best reach (the ceilings quoted in the header of attn_bf16.hip).
 //
 //   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops \
 //         -o mfma_lds_rates paper_2507_10069_amd/csrc/mfma_lds_rates.hip && ./mfma_lds_rates

@@ -3,7 +3,7 @@
 // instructions of one kind after each MFMA, everything written as inline assembly so that the stream is
 // exactly the written one.  One workgroup per XCD, so the clock stays at its nominal 2.4 GHz and the
 // numbers are cycles, not power.  Two waves per SIMD (512 threads) and one (256 threads).
-// Source of the issue-cost model quoted in the design doc and in the header of attn_bf16.hip.
+// Source of the issue-cost model quoted in the header of attn_bf16.hip.
 //
 //   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops \
 //         -o valu_issue_costs paper_2507_10069_amd/csrc/valu_issue_costs.hip && ./valu_issue_costs
