@@ -37,7 +37,8 @@
 // (ring slot) so buffer offsets and register roles are compile-time constants.
 //
 // Work units left over after an XCD's full rounds of 32 are cut along the key axis and merged by
-// attn_bf16_merge_kernel (see "Work units" below).
+// attn_bf16_merge_kernel or, when too short for that, halved along their rows: two workgroups with four
+// working waves each (see "Work units" below).  A wave without rows of its own only fetches.
 //
 // Cost model (measured on gfx950): per MFMA of 32 cycles the SIMD's VALU issue port is taken ~13 cycles
 // by the MFMA itself, ~4.3 by each plain VALU instruction, ~8.6 by v_exp_f32, and ~5.6 per KiB of LDS
