@@ -852,6 +852,9 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
         hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, L);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || !L.split) return err;
+    // no context of this batch is long enough for two pieces along the keys: left-over units can only have been
+    // halved along their rows, which leaves nothing to merge
+    if ((long long)b.max_pages * 16 < 2ll * MIN_TILES_PER_PART * BC) return err;
     hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * MAX_TAIL), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }
