@@ -368,6 +368,47 @@ def test_random_decode_batches(seed):
         assert bits(dw.v_cache).tobytes() == bits(ref.v_cache).tobytes()
 
 
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library only launches kernels on the given stream (no allocation, no memset, no synchronisation), so a
+    step can be captured in a HIP graph; every replay, with eager work between the replays, must reproduce the
+    eager result bit for bit -- prefill (with cut units and the merge kernel), decode with units, and the fused step."""
+    print("case graph capture", flush=True)
+    bits = B.DeviceWorkload.to_numpy_bits
+    prefill = W.build_workload("graph_prefill", "causal", "bf16", 1700, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                               page_size=16, prefix_lens=[5000, 300], new_lens=[64, 200])
+    decode = W.build_workload("graph_decode", "causal", "bf16", 1701, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                              page_size=16, prefix_lens=[2100, 2200, 900, 40], new_lens=[1, 1, 1, 1],
+                              share_group=[0, 0, 1, 2], shared_len=[2048, 2048, 0, 0])
+    for wl, step in ((prefill, lambda d: d.step()), (decode, lambda d: (d.scatter(), d.attention_shared())),
+                     (decode, lambda d: d.decode_step(True))):
+        eager = _gpu_run(wl)
+        if wl is decode:
+            eager.plan_shared()
+            eager.out.zero_()
+            step(eager)
+            torch.cuda.synchronize()
+        want_out, want_k = bits(eager.out).tobytes(), bits(eager.k_cache).tobytes()
+        dw = B.DeviceWorkload(wl)
+        if wl is decode:
+            dw.plan_shared()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step(dw)                                    # warm up on the capture stream
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step(dw)
+        for replay in range(3):
+            dw.out.zero_()                              # eager work and a synchronisation between the replays
+            if dw.workspace is not None:
+                dw.workspace.fill_(0x5A)                # stale workspace contents must not matter
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert bits(dw.out).tobytes() == want_out, replay
+            assert bits(dw.k_cache).tobytes() == want_k, replay
+
+
 def test_kv_page_migration_is_exact_and_checksummed():
     """Appendix B.5 on one GPU: a request's pages are packed, checksummed, unpacked into other pages of another
     pool; bytes and Adler-32 values must equal the reference's, a corrupted buffer must be reported, and decode
