@@ -75,6 +75,15 @@ def cpu_baseline(wl, target_tokens):
             "new_tokens_per_s": len(tokens) / dt}
 
 
+def read_decode_traffic(name):
+    """HBM bytes per launch of the decode main kernel measured with rocprofv3 --pmc (see profiles/), if recorded."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "attn_bf16_decode_hbm_traffic.json")) as f:
+            return json.load(f).get(name, {}).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
 def read_traffic():
     """HBM bytes per attention launch measured with rocprofv3 --pmc (see profiles/), if recorded."""
     path = os.path.join(ROOT, "profiles", "attn_bf16_cfg3_hbm_traffic.json")
@@ -318,7 +327,7 @@ def main():
                        "parallelism": "single-gpu"},
             "new_tokens_per_s": wl.total_new_tokens / (ms * 1e-3), "attention_ms": attn_ms, "scatter_ms": scat_ms,
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                         "frac": gbs / HBM_PEAK_GBS, "traffic": read_decode_traffic(wl.name),
                          "kernel": "attn_bf16_decode_kernel + attn_bf16_decode_merge_kernel"},
             "shared_prefix": shared, "fused_step_ms": fused,
         }), flush=True)
