@@ -319,6 +319,24 @@ def main():
             fused[key] = max(e0.elapsed_time(e1), (time.perf_counter() - t0) * 1e3) / args.steps
         log("  step as one call (emm_decode_step): %.4f ms plain (scatter + attention: %.4f), %.4f ms planned (%.4f)"
             % (fused["plain"], fused["plain_two_calls"], fused["planned"], fused["planned_two_calls"]))
+        # the planned step captured in a HIP graph and replayed: what a serving loop that captures its layers sees
+        side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            dw.decode_step(True)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                dw.decode_step(True)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        fused["planned_graph_replay"] = e0.elapsed_time(e1) / args.steps
+        log("  the planned step replayed from a HIP graph: %.4f ms" % fused["planned_graph_replay"])
         print(json.dumps({
             "metric": "decode_attention_kv_read_gbs", "value": wl.kv_read_bytes() / (ms * 1e-3) / 1e9, "unit": "GB/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
