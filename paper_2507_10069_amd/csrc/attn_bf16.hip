@@ -93,11 +93,15 @@ __device__ inline void static_for(F&& f)
 // a workspace is given, each of those tail units is cut into 2 or 4 pieces of equal key range, done by
 // separate workgroups, so that the final round fills the XCD; a piece writes its unnormalised accumulator,
 // running maximum and row sum to the workspace and a second, small kernel merges the pieces of a unit.
+// An XCD with fewer units than compute units -- few requests with few new tokens each, the usual case after
+// a long cached prefix -- has nothing but a "final round": its units are cut into up to 16 pieces each, as
+// many as fill the XCD, so that the latency of a long context is spread over the chip.
 // Which units are cut follows from the batch's lengths alone, so every workgroup of either kernel derives
 // the same plan by itself: no flags, counters or descriptors are exchanged.
 constexpr int CU_PER_XCD = 32;
-constexpr int MAX_PARTS = 4;
-constexpr int MAX_TAIL = CU_PER_XCD - 1;                 // tail units per XCD
+constexpr int MAX_PARTS = 16;                            // pieces per unit at most
+constexpr int PIECES_PER_XCD = CU_PER_XCD;               // tail units x pieces of an XCD never exceed its compute units
+constexpr int EXTRA_PER_XCD = CU_PER_XCD - 1;            // workgroups for pieces 1, 2, ... of an XCD's tail units
 constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 32;              // planning scans an XCD's pairs: keep that short
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
@@ -119,18 +123,25 @@ struct UnitPlan {
     bool rows_only;         // parts == 2 stands for a halving along the rows only (never a cut along the keys)
 };
 
-__host__ __device__ inline int split_factor_of(int rem)  // pieces per tail unit when rem units are left over
+// pieces per tail unit when rem units are left over after full_rounds rounds of 32
+__host__ __device__ inline int split_factor_of(int rem, int full_rounds)
 {
+    if (rem == 0) return 1;
+    if (full_rounds == 0) {
+        // the whole XCD is under-filled: as many pieces per unit as fill it (1-2 units: 16, 3-4: 8, 5-8: 4, 9-16: 2)
+        int p = 1;
+        while (p < MAX_PARTS && 2 * p * rem <= CU_PER_XCD) p *= 2;
+        return p;
+    }
     // With more leftover units the compute units that stay idle in the last round are few, and the busy
     // ones run at a higher clock for it (the chip is power limited): cutting then costs more than it gains.
-    if (rem == 0 || rem > 12) return 1;
+    if (rem > 12) return 1;
     return rem > 8 ? 2 : 4;
 }
 // 13 .. 16 leftover units are not cut along the keys (see above) but still halved along their rows: the 26 .. 32
 // halves fill the XCD's last round, cost nothing to merge, and each finishes in about 60 % of a unit's time
 __host__ __device__ inline bool rows_only_of(int rem) { return rem > 12 && rem <= CU_PER_XCD / 2; }
-__device__ inline int split_factor(int rem) { return rows_only_of(rem) ? 2 : split_factor_of(rem); }
-inline int host_split_factor(int rem) { return rows_only_of(rem) ? 2 : split_factor_of(rem); }
+__host__ __device__ inline int split_factor(int rem, int full_rounds) { return rows_only_of(rem) ? 2 : split_factor_of(rem, full_rounds); }
 
 // row tiles (units) of sub-pair sp
 __host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int sp)
@@ -148,6 +159,13 @@ __device__ inline bool cuttable(int n_tiles, int parts, int limit_min)
     const int last_begin = (parts - 1) * n_tiles / parts;
     return n_tiles >= MIN_TILES_PER_PART * parts && (last_begin + 1) * BC - 1 <= limit_min;
 }
+// Into how many pieces a unit planned for `parts` pieces is really cut: the largest power of two up to `parts`
+// that it can be cut into (1: not at all).  Every workgroup concerned with the unit finds the same number.
+__device__ inline int pieces_cut(int n_tiles, int parts, int limit_min)
+{
+    while (parts > 1 && !cuttable(n_tiles, parts, limit_min)) parts >>= 1;
+    return parts;
+}
 
 __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31 (and, separately, 32..63)
 {
@@ -157,14 +175,16 @@ __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31
 }
 
 // Plan of workgroup `in_xcd` of XCD `xcd`.  Regular workgroups come first (pair-major, row tiles descending,
-// as many slots per pair as the longest request needs), then 3 x 31 workgroups for pieces 1..3 of tail units.
+// as many slots per pair as the longest request needs), then 31 workgroups for pieces 1, 2, ... of tail units.
 // The scan over the XCD's pairs (at most 32 when cutting is enabled) is done by the lanes of each wave.
-__device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd)
+// merge_idx >= 0 asks instead, whatever in_xcd is, for the plan of merge workgroup merge_idx of the XCD: the unit
+// in tail slot merge_idx / parts, with .part = merge_idx % parts.
+__device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd, int merge_idx = -1)
 {
     UnitPlan u;
     u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false;
     const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
-    const bool regular = in_xcd < n_regular;
+    const bool regular = merge_idx < 0 && in_xcd < n_regular;
     const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
     int my_cnt = 0, my_idx = 0;
     if (regular) {
@@ -187,7 +207,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
                         ? sub_pair_tiles(b.new_lens[lane_sp / L.fan / b.num_kv_heads], G, L.fan, lane_sp) : 0;
     const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
     const int rem = total % CU_PER_XCD;
-    const int parts = split_factor(rem);
+    const int parts = split_factor(rem, total / CU_PER_XCD);
     if (parts == 1) return u;
     u.rows_only = rows_only_of(rem);                            // regular: whole unit; extra: nothing to do (pair < 0)
     const int first_tail = total - rem;
@@ -201,8 +221,8 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
         return u;
     }
     const int e = in_xcd - n_regular;
-    const int slot = e / (MAX_PARTS - 1), part = 1 + e % (MAX_PARTS - 1);
-    if (slot >= rem || part >= parts) return u;
+    const int slot = merge_idx >= 0 ? merge_idx / parts : e / (parts - 1), part = merge_idx >= 0 ? merge_idx % parts : 1 + e % (parts - 1);
+    if (slot >= rem) return u;
     const int ordinal = first_tail + slot;
     // the pair that holds this ordinal: the first one whose inclusive running count exceeds it
     int incl = cnt;
@@ -224,10 +244,10 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     return u;
 }
 
-// workspace of pieces: [xcd][tail slot][piece][66][512] floats
-__device__ inline float* part_base(void* workspace, int xcd, int slot, int part)
+// workspace of pieces: [xcd][tail slot x planned pieces per unit + piece][66][512] floats
+__device__ inline float* part_base(void* workspace, int xcd, int slot, int parts, int part)
 {
-    return (float*)workspace + (size_t)((xcd * MAX_TAIL + slot) * MAX_PARTS + part) * PART_FLOATS;
+    return (float*)workspace + (size_t)(xcd * PIECES_PER_XCD + slot * parts + part) * PART_FLOATS;
 }
 
 template <bool CAUSAL>
@@ -265,16 +285,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // fetch.  Rows are independent, so nothing has to be merged, and with one working wave per SIMD a tile
     // takes about 60 % of the time.  (With at most half a tile of rows there is nothing to halve.)
     int row_half = -1;                                       // -1: all eight waves work on their rows
-    if (plan.parts > 1 && (plan.rows_only || !cuttable(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1))) {
+    // into how many pieces the unit is really cut along the keys: as planned for its XCD, fewer if it is too
+    // short for that, 1 if it cannot be cut at all or is only to be halved
+    const int cut = (plan.parts > 1 && !plan.rows_only) ? pieces_cut(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1) : 1;
+    if (plan.parts > 1 && cut == 1) {
         const bool halve = n_rows - row0 > BR / 2;
         if (plan.part > (halve ? 1 : 0)) return;
         if (halve) row_half = plan.part;
-        plan.parts = 1;
         plan.part = 0;
+    } else if (plan.part >= cut) {
+        return;
     }
     // this workgroup's key tiles: t_begin .. t_begin + n_tiles - 1
-    const int t_begin = plan.part * n_tiles_unit / plan.parts;
-    const int n_tiles = (plan.part + 1) * n_tiles_unit / plan.parts - t_begin;
+    const int t_begin = plan.part * n_tiles_unit / cut;
+    const int n_tiles = (plan.part + 1) * n_tiles_unit / cut - t_begin;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -701,10 +725,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     {
         int t2 = threadIdx.x;
         asm volatile("" : "+v"(t2));
-        if (plan.parts > 1) {
+        if (cut > 1) {
             // a piece of a cut unit: unnormalised accumulator, running maximum and row sum go to the
             // workspace, one coalesced row of 512 floats per register; attn_bf16_merge_kernel finishes
-            float* __restrict__ ws = part_base(a.workspace, xcd, plan.slot, plan.part) + t2;
+            float* __restrict__ ws = part_base(a.workspace, xcd, plan.slot, plan.parts, plan.part) + t2;
             const float l_part = pair_sum(l_run);
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
@@ -739,15 +763,69 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     }
 }
 
-// Merges the pieces of the cut units: one workgroup per (XCD, tail slot), thread for thread the layout of
-// the main kernel's epilogue.  Workgroups whose slot holds no cut unit leave at once.
+// One workgroup's share of the merge of a unit planned for PARTS pieces and cut into `cut` of them: 64 / PARTS
+// of each thread's 64 accumulator registers, in groups of four (one 8-byte store each).  Every load is issued
+// whatever `cut` is (pieces past the last repeat it, with weight 0) so that all of them are in flight at once.
+template <int PARTS>
+__device__ inline void merge_share(const float* __restrict__ ws0, int cut, int sub, float scale, __bf16* __restrict__ op,
+                                   int h32, float* __restrict__ lse)
+{
+    const float c_log2 = scale * 1.44269504088896340736f;
+    float m_part[PARTS], l_part[PARTS], w[PARTS];
+    size_t off[PARTS];
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < PARTS; ++j) {
+        off[j] = (size_t)min(j, cut - 1) * PART_FLOATS;
+        m_part[j] = ws0[off[j] + 64 * NTHREADS];
+        l_part[j] = ws0[off[j] + 65 * NTHREADS];
+    }
+#pragma unroll
+    for (int j = 0; j < PARTS; ++j) {
+        if (j >= cut) m_part[j] = -INFINITY;
+        m_all = fmaxf(m_all, m_part[j]);
+    }
+    float l_tot = 0.f;
+#pragma unroll
+    for (int j = 0; j < PARTS; ++j) {
+        w[j] = __builtin_amdgcn_exp2f((m_part[j] - m_all) * c_log2);
+        l_tot += w[j] * l_part[j];
+    }
+    const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
+    constexpr int N4 = 16 / PARTS;                           // groups of four registers in this share
+    float acc[N4][4];
+#pragma unroll
+    for (int i = 0; i < N4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < PARTS; ++j)
+#pragma unroll
+        for (int i = 0; i < N4; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][e] += w[j] * ws0[off[j] + (size_t)(4 * (sub * N4 + i) + e) * NTHREADS];
+#pragma unroll
+    for (int i = 0; i < N4; ++i) {
+        // registers 4g .. 4g+3 of a thread are channels 32 (g / 4) + 8 (g % 4) + 4 h32 + 0..3
+        const int g = sub * N4 + i;
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[i][e] * inv);
+        *(bf16x4*)(op + 32 * (g >> 2) + 8 * (g & 3) + 4 * h32) = o;
+    }
+    if (lse != nullptr) *lse = (l_tot > 0.f) ? m_all * scale + logf(l_tot) : -INFINITY;
+}
+
+// Merges the pieces of the cut units, thread for thread the layout of the main kernel's epilogue.  An XCD
+// whose tail units are planned for p pieces each gets 32 workgroups: number k works on tail slot k / p and
+// there on share k % p of the 64 accumulator registers, so every workgroup reads the same 64 rows of 2 KB
+// whatever p is.  Workgroups whose slot holds no cut unit leave at once.
 __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, LaunchShape L)
 {
     const BatchView& b = a.b;
     const int G = b.num_q_heads / b.num_kv_heads;
-    const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD;
-    // the plan of the workgroup that did piece 1 of this slot names the unit
-    const UnitPlan plan = plan_unit(b, G, L, xcd, L.pairs_per_xcd * L.n_row_tiles + slot * (MAX_PARTS - 1));
+    const int xcd = blockIdx.x % NUM_XCD;
+    const UnitPlan plan = plan_unit(b, G, L, xcd, 0, blockIdx.x / NUM_XCD);   // .part is this workgroup's share
     if (plan.pair < 0) return;
     const int kvh = plan.pair % b.num_kv_heads;
     const int r = plan.pair / b.num_kv_heads;
@@ -757,60 +835,32 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int P = b.prefix_lens[r];
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = a.causal ? P + last_row / G + 1 : P;
-    if (plan.rows_only || !cuttable((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1)) return;   // not cut along the keys
+    const int cut = plan.rows_only ? 1 : pieces_cut((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1);
+    if (cut == 1) return;                                    // not cut along the keys
 
     const int tid = threadIdx.x;
-    const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
-    const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, 0) + tid;
-    float m_part[MAX_PARTS], w[MAX_PARTS];
-    float m_all = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < MAX_PARTS; ++j) {
-        m_part[j] = (j < plan.parts) ? ws0[(size_t)j * PART_FLOATS + 64 * NTHREADS] : -INFINITY;
-        m_all = fmaxf(m_all, m_part[j]);
-    }
-    float l_tot = 0.f;
-#pragma unroll
-    for (int j = 0; j < MAX_PARTS; ++j) {
-        w[j] = (j < plan.parts) ? __builtin_amdgcn_exp2f((m_part[j] - m_all) * c_log2) : 0.f;
-        if (j < plan.parts) l_tot += w[j] * ws0[(size_t)j * PART_FLOATS + 65 * NTHREADS];
-    }
     const int l32 = tid & 31, h32 = (tid >> 5) & 1;
     const int row = row0 + (tid >> 6) * 32 + l32;
     if (row >= n_rows) return;
     const int tok = row / G;
     const int hq = kvh * G + (row - tok * G);
     const long long q_row = (long long)b.cu_new_lens[r] + tok;
-    const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
+    const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, plan.parts, 0) + tid;
     __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
-#pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-        float acc[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
-        for (int j = 0; j < MAX_PARTS; ++j)
-            if (j < plan.parts) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] += w[j] * ws0[(size_t)j * PART_FLOATS + (16 * nb + v) * NTHREADS];
-            }
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[4 * v4 + e] * inv);
-            *(bf16x4*)(op + 32 * nb + 8 * v4 + 4 * h32) = o;
-        }
+    float* lse = (a.lse != nullptr && h32 == 0 && plan.part == 0) ? a.lse + q_row * b.num_q_heads + hq : nullptr;
+    switch (plan.parts) {
+        case 2: merge_share<2>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 4: merge_share<4>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 8: merge_share<8>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        default: merge_share<16>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
     }
-    if (a.lse != nullptr && h32 == 0)
-        a.lse[q_row * b.num_q_heads + hq] = (l_tot > 0.f) ? m_all * b.softmax_scale + logf(l_tot) : -INFINITY;
 }
 
 }  // namespace
 
 size_t attn_bf16_d128_workspace_bytes()
 {
-    return (size_t)NUM_XCD * MAX_TAIL * MAX_PARTS * PART_FLOATS * sizeof(float);
+    return (size_t)NUM_XCD * PIECES_PER_XCD * PART_FLOATS * sizeof(float);
 }
 
 hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
@@ -839,11 +889,11 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
         for (int x = 0; x < NUM_XCD; ++x) {
             long long units = 0;
             for (long long sp = x; sp < n_pairs; sp += NUM_XCD) units += sub_pair_tiles(b.max_new_len, G, fan, (int)sp);
-            any = any || host_split_factor((int)(units % CU_PER_XCD)) > 1;
+            any = any || split_factor((int)(units % CU_PER_XCD), (int)(units / CU_PER_XCD)) > 1;
         }
         if (!any) L.split = 0;
     }
-    const long long per_xcd = pairs_per_xcd * n_row_tiles + (L.split ? MAX_TAIL * (MAX_PARTS - 1) : 0);
+    const long long per_xcd = pairs_per_xcd * n_row_tiles + (L.split ? EXTRA_PER_XCD : 0);
     const long long grid = NUM_XCD * per_xcd;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)
@@ -855,7 +905,7 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     // no context of this batch is long enough for two pieces along the keys: left-over units can only have been
     // halved along their rows, which leaves nothing to merge
     if ((long long)b.max_pages * 16 < 2ll * MIN_TILES_PER_PART * BC) return err;
-    hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * MAX_TAIL), dim3(NTHREADS), 0, stream, a, L);
+    hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * PIECES_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }
 

@@ -117,9 +117,14 @@ def test_ragged_cross_sweep():
 # 16 key tiles and starts below the diagonal.
 CUT_CASES = [
     # name, kind, H, Hkv, prefix lens, new lens
-    ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 2 units per XCD on 4 XCDs, 4 pieces each
+    ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 1 unit per XCD, planned for 16 pieces; 80 tiles give 4
     ("cut2_causal", "causal", 28, 4, [2100], [350]),                # 10 units per XCD, 2 pieces each
-    ("cut4_cross", "cross", 32, 8, [6404, 6404], [100, 37]),        # 3 units per XCD, 4 pieces; ragged last tile
+    ("cut4_cross", "cross", 32, 8, [6404, 6404], [100, 37]),        # 3 units per XCD, 8 planned, 4 cut; ragged last tile
+    ("cut16_causal", "causal", 28, 4, [17000], [36]),               # 1 unit on every other XCD, 267 tiles: 16 pieces
+    ("cut16_cross", "cross", 32, 8, [16500], [30]),                 # 1 unit per XCD of 120 rows, 258 tiles: 16 pieces
+    ("cut8_causal", "causal", 28, 4, [9000, 9100], [36, 20]),       # 1 unit per XCD, 142-143 tiles: 8 pieces
+    ("cut8_planned", "causal", 32, 8, [8200, 8300, 9000], [50, 64, 3]),   # 3 units per XCD, 8 pieces each
+    ("cut_2units", "causal", 16, 8, [16400, 16400], [130, 7]),      # 2 and 1 units per XCD, 16 pieces each
     ("cut_mixed", "causal", 16, 8, [8000, 100, 4100], [64, 200, 3]),  # long units are cut, short ones are not
     ("cut_edge", "causal", 8, 8, [4091, 4096, 4000, 1800], [5, 5, 200, 300]),  # 64 tiles: just cut; 63: not cut;
                                                                     # a last piece that would start on the diagonal
