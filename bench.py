@@ -390,6 +390,16 @@ def main():
                               "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
             log("workload %s: %s" % (w.name, others[w.name]))
             del d
+        for name in W.SUFFIX_CONFIGS:                    # short suffixes after a large cache hit
+            w = W.suffix_config(name)
+            d = B.DeviceWorkload(w)
+            m, am, sm = time_workload(d, 30, 5)
+            others[name] = {"ms_per_step": m, "attention_ms": am, "scatter_ms": sm,
+                            "tflops": w.attention_flops() / (am * 1e-3) / 1e12,
+                            "kv_read_gbs": w.kv_read_bytes() / (am * 1e-3) / 1e9,
+                            "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
+            log("workload %s: %s" % (name, others[name]))
+            del d
         for name in W.DECODE_CONFIGS:
             w = W.decode_config(name)
             d = B.DeviceWorkload(w)

@@ -344,6 +344,22 @@ def decode_config(name: str, shrink: int = 1) -> Workload:
                           shared_len=shared_len, spare_pages=8)
 
 
+def suffix_config(name: str, shrink: int = 1) -> Workload:
+    """Prefill batches as they look after a large prefix-cache hit: a long cached context and a short new
+    suffix (the question about a video or image that was seen before), 28/4 heads.  Few rows, many keys:
+    the latency of the long context has to be spread over the chip by cutting along the keys.
+      suffix_b1_16k_n36   1 request, 16384 cached + 36 new tokens
+      suffix_b8_16k_n36   8 requests of that shape (private pages)
+      suffix_b8_16k_n4    8 requests, 16384 cached + 4 new tokens
+      suffix_b32_4k_n36   32 requests, 4096 cached + 36 new tokens"""
+    shapes = {"suffix_b1_16k_n36": (1, 16384, 36, 2101), "suffix_b8_16k_n36": (8, 16384, 36, 2102),
+              "suffix_b8_16k_n4": (8, 16384, 4, 2103), "suffix_b32_4k_n36": (32, 4096, 36, 2104)}
+    n_req, P, N, seed = shapes[name]
+    return build_workload(name, "causal", "bf16", seed, num_q_heads=28, num_kv_heads=4, head_dim=128, page_size=16,
+                          prefix_lens=[_s(P, shrink)] * n_req, new_lens=[N] * n_req, spare_pages=8)
+
+
+SUFFIX_CONFIGS = ("suffix_b1_16k_n36", "suffix_b8_16k_n36", "suffix_b8_16k_n4", "suffix_b32_4k_n36")
 DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k", "decode_b1_16k", "decode_b1_128k")
 DECODE_SHARED_CONFIGS = ("decode_shared_video_b8", "decode_shared_video_b32", "decode_shared_image_b32")
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}

@@ -80,6 +80,17 @@ def test_full_size_sampled_parity(cfg, n):
     print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
 
 
+@pytest.mark.parametrize("name", W.SUFFIX_CONFIGS)
+def test_suffix_after_cache_hit_sampled_parity(name):
+    """Short suffixes over long cached contexts at the sizes bench.py --others times: every unit is cut into
+    2 .. 16 pieces (or halved) because no XCD has a full round of units."""
+    print("case", name, flush=True)
+    wl = W.suffix_config(name)
+    dw = _gpu_run(wl)
+    tokens = None if wl.total_new_tokens <= 40 else _sample_tokens(wl, 24, seed=len(name))
+    print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
+
+
 RAGGED = [(0, 1), (0, 2), (0, 33), (1, 1), (15, 31), (16, 32), (17, 33), (63, 127), (64, 128), (65, 129),
           (200, 300), (0, 129), (127, 1), (128, 64), (1000, 7)]
 
@@ -114,7 +125,8 @@ def test_ragged_cross_sweep():
 # Batches whose last work units are cut along the key axis and merged by the second kernel.  A unit is a
 # 256-row tile of one (request, KV head) pair; pairs are dealt to the 8 XCDs; the units an XCD has left over
 # after its full rounds of 32 are cut into 4 pieces (1..8 left over) or 2 (9..12) when every piece gets at least
-# 16 key tiles and starts below the diagonal.
+# 16 key tiles and starts below the diagonal; an XCD without a full round cuts into as many pieces as fill it,
+# up to 16.
 CUT_CASES = [
     # name, kind, H, Hkv, prefix lens, new lens
     ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 1 unit per XCD, planned for 16 pieces; 80 tiles give 4
