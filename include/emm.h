@@ -32,8 +32,8 @@
  *     [T][num_kv_heads][head_dim]; rows of request r are cu_new_lens[r] .. cu_new_lens[r+1]-1.
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
  *   - Element offsets are computed in 64 bits.
- *   - Supported: page_size 16; EMM_BF16 with head_dim 128 (MFMA kernels); EMM_F32 with head_dim 64
- *     or 128 (plain fp32 kernels).  Anything else returns EMM_ERR_UNSUPPORTED.
+ *   - Supported: page_size 16, 32, 64, 128 or 256; EMM_BF16 with head_dim 128 (MFMA kernels); EMM_F32
+ *     with head_dim 64 or 128 (plain fp32 kernels).  Anything else returns EMM_ERR_UNSUPPORTED.
  *   - A page that receives new tokens must be referenced by exactly one request: shared pages
  *     (prefix-tree nodes with several users, Appendix A) are read-only.
  */

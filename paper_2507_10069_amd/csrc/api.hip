@@ -32,7 +32,8 @@ emm_status check_scalars(const emm_batch* b)
 
 emm_status check_supported(const emm_batch* b)
 {
-    if (b->page_size != 16) return EMM_ERR_UNSUPPORTED;
+    if (b->page_size != 16 && b->page_size != 32 && b->page_size != 64 && b->page_size != 128 && b->page_size != 256)
+        return EMM_ERR_UNSUPPORTED;
     if (b->dtype == EMM_BF16 && b->head_dim != 128) return EMM_ERR_UNSUPPORTED;
     if (b->dtype == EMM_F32 && b->head_dim != 64 && b->head_dim != 128) return EMM_ERR_UNSUPPORTED;
     return EMM_OK;
@@ -59,6 +60,8 @@ emm::BatchView view_of(const emm_batch* b)
     v.num_kv_heads = b->num_kv_heads;
     v.head_dim = b->head_dim;
     v.page_size = b->page_size;
+    v.page_shift = 0;
+    while ((16 << v.page_shift) < b->page_size) ++v.page_shift;
     v.num_pages = b->num_pages;
     v.max_pages = b->max_pages_per_req;
     v.total_new_tokens = b->total_new_tokens;

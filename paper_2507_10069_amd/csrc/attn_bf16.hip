@@ -1,4 +1,4 @@
-// bf16 MFMA flash-style attention over the paged KV pool, head_dim 128, page size 16, for gfx950.
+// bf16 MFMA flash-style attention over the paged KV pool, head_dim 128, pages of 16 to 256 tokens, for gfx950.
 //
 // Computes, for every new token of every request, softmax(scale * q K^T) V over the request's
 // logical key range read through the page table: cached prefix plus the new tokens up to the
@@ -10,9 +10,9 @@
 //               G query heads that share a KV head are neighbours and consume the same K/V tile;
 //   workgroup = 8 waves = 256 consecutive rows of one (request, KV head); 2 waves per SIMD;
 //   wave      = 32 rows, all 128 channels;
-//   KV loop   = tiles of 64 keys (4 pages), in logical order.
-// Per tile the 4 pages of K and of V for the KV head go straight from L2/HBM into LDS (LDS-DMA loads,
-// 16 bytes per lane, whole 4 KB page slabs), row-major with XOR-swizzled 16-byte chunks; K is consumed
+//   KV loop   = tiles of 64 keys (4 blocks of 16 keys; a page holds 1 to 16 blocks), in logical order.
+// Per tile the 4 blocks of K and of V for the KV head go straight from L2/HBM into LDS (LDS-DMA loads,
+// 16 bytes per lane, whole 4 KB slabs), row-major with XOR-swizzled 16-byte chunks; K is consumed
 // with ds_read_b128, V with the transposing ds_read_b64_tr_b16, both by v_mfma_f32_32x32x16_bf16.
 //
 // Orientation.  Scores are produced transposed, S^T = K Q^T, so that an accumulator lane owns ONE
@@ -20,7 +20,7 @@
 // in lane l^32.  Row max and row sum need in-lane work plus one exchange with the partner lane.
 // The output is accumulated transposed as well, O^T = V^T P^T, so the same lane owns the same row
 // there and the online-softmax rescale is a per-lane scalar.  K rows are stored in LDS with bits 2
-// and 3 of the in-page key index swapped; with that placement accumulator registers 8s..8s+7 of a
+// and 3 of the in-block key index swapped; with that placement accumulator registers 8s..8s+7 of a
 // lane are exactly the 8 consecutive keys the B operand of the value product expects from it, so
 // P goes from the score accumulators to the PV operand without leaving registers.
 //
@@ -327,17 +327,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // ---- global -> LDS.  Tiles go straight from global memory into LDS (global_load_lds_dwordx4: lane i
     //      of a wave writes 16 bytes at base + 16 i), 4 rows of 256 bytes per instruction.  Wave w brings
     //      rows 8w .. 8w+7 of the K tile and of the V tile (two instructions each), all from logical
-    //      page 4 kt + w/2.  Placement is row-major with 16-byte chunks XOR-swizzled; since the hardware
+    //      16-key block 4 kt + w/2.  Placement is row-major with 16-byte chunks XOR-swizzled; since the hardware
     //      fixes where a lane's bytes land, the swizzle (and for K the row permutation) is applied on
     //      the source side: the lane that lands on (row, physical chunk p) fetches logical chunk
     //      p ^ f(row) of the key that belongs in that row.
-    //        K: row = 16 page + swap23(key in page), f(row) = row & 15   (read with ds_read_b128)
+    //        K: row = 16 block + swap23(key in block), f(row) = row & 15   (read with ds_read_b128)
     //        V: row = key,                           f(row) = (row & 3) << 2   (read with ds_read_tr16_b64)
-    //      Page indices past the request's last page are clamped to it (branch-free): K rows fetched
+    //      Block indices past the request's last block are clamped to it (branch-free): K rows fetched
     //      that way give scores the mask removes; V rows past the request's tokens are zeroed in LDS by
     //      the wave that fetched them (zero_v_tail), because 0 * NaN would poison the output.
     const int ld_row = lane >> 4, ld_p = lane & 15;          // row within the 4-row group, physical chunk
-    // byte offsets inside a (page, head) slab of what this lane fetches first (rows 8(w&1) + ld_row); the
+    // byte offsets inside a (block, head) slab of what this lane fetches first (rows 8(w&1) + ld_row); the
     // second fetch (4 rows further down) is derived: for K the key moves by 8 and chunk bit 2 flips, for
     // V the row moves by 4
     const int r16 = 8 * (wave & 1) + ld_row;
@@ -345,24 +345,23 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int v_goff0 = r16 * 256 + ((ld_p ^ ((r16 & 3) << 2)) << 4);
     const unsigned char* __restrict__ kcb = (const unsigned char*)a.k_cache;
     const unsigned char* __restrict__ vcb = (const unsigned char*)a.v_cache;
-    const long long slab_bytes = (long long)b.num_kv_heads * 4096;   // one page, all heads
-    const long long head_bytes = (long long)kvh * 4096;
-    const int n_pages_valid = (ctx_len + 15) >> 4;
+    const int n_blocks_valid = (ctx_len + 15) >> 4;          // 16-key blocks (4096 bytes per KV head in the pool)
     const int ld_lds = wave * 8 * 256;                       // LDS byte offset of this wave's rows in a tile
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
 
-    // Page ids: lane k of a wave holds the physical page this wave fetches for tile pg_base + k (logical
-    // page 4 (pg_base + k) + wave/2), refilled every 63 tiles; a tile's id is moved to an SGPR with
+    // Block ids: lane k of a wave holds, in units of 4096 bytes, where in the pool the 16-key block lies that
+    // this wave fetches for tile pg_base + k (logical block 4 (pg_base + k) + wave/2 of this KV head; a page
+    // is 2^page_shift such blocks); refilled every 63 tiles; a tile's id is moved to an SGPR with
     // v_readlane.  (A scalar load per tile would sit behind the LDS-DMA loads in program order.)
     int pg_vec = 0, pg_base = 0;
     auto refill_pages = [&](int kt0) {
-        const int lp = min((kt0 + lane) * 4 + (wave >> 1), n_pages_valid - 1);
-        pg_vec = min(max(pt[lp], 0), b.num_pages - 1);       // never leave the pool
+        const int blk = min((kt0 + lane) * 4 + (wave >> 1), n_blocks_valid - 1);
+        const int page = min(max(pt[blk >> b.page_shift], 0), b.num_pages - 1);       // never leave the pool
+        pg_vec = ((page * b.num_kv_heads + kvh) << b.page_shift) + (blk & ((1 << b.page_shift) - 1));
         pg_base = kt0;
     };
-    auto slab_of = [&](int kt) -> long long {                // byte offset of (page of tile kt, this KV head)
-        const int page = __builtin_amdgcn_readlane(pg_vec, kt - pg_base);
-        return (long long)page * slab_bytes + head_bytes;
+    auto slab_of = [&](int kt) -> long long {                // byte offset of this wave's block of tile kt
+        return (long long)__builtin_amdgcn_readlane(pg_vec, kt - pg_base) * 4096;
     };
     auto load_k = [&](int kt, int kbuf) {
         const unsigned char* src = kcb + slab_of(kt);
@@ -904,7 +903,7 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     if (err != hipSuccess || !L.split) return err;
     // no context of this batch is long enough for two pieces along the keys: left-over units can only have been
     // halved along their rows, which leaves nothing to merge
-    if ((long long)b.max_pages * 16 < 2ll * MIN_TILES_PER_PART * BC) return err;
+    if ((long long)b.max_pages * b.page_size < 2ll * MIN_TILES_PER_PART * BC) return err;
     hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * PIECES_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }

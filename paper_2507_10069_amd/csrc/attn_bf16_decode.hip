@@ -1,4 +1,4 @@
-// Decode-step attention over the paged KV pool (bf16, head_dim 128, page size 16) for gfx950: every
+// Decode-step attention over the paged KV pool (bf16, head_dim 128, pages of 16 to 256 tokens) for gfx950: every
 // request has at most ONE query token, which attends to its whole context -- the stage that follows
 // prefill and produces one token per iteration (Section 2.2 of the paper; memory bound, as it says).
 // Same operation as the prefill kernel restricted to one row tile of G = H / Hkv rows per (request,
@@ -42,7 +42,7 @@ constexpr int MAX_G = 16;                        // query heads per KV head this
 constexpr int REC_FLOATS = D + 2;                // per row of a record: 128 accumulator values, m, l
 constexpr int NW = 4;                            // waves per workgroup
 constexpr int NT = NW * 64;
-constexpr int BK = 32;                           // keys per tile: two pages
+constexpr int BK = 32;                           // keys per tile: two 16-key blocks (a page holds 1 to 16 blocks)
 constexpr int TILE_BYTES = BK * D * 2;           // one K or V tile in LDS: 32 rows of 256 bytes
 constexpr int NSLOT = 3;                         // ring depth; tile i of a piece lives in slot i % NSLOT
 constexpr int AHEAD = 2;                         // tiles in flight beyond the one being computed
@@ -103,12 +103,13 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int lane = tid & 63;
     const int t_off = (SHARED && !unit_mode) ? sv.req_shared_len[r] / BK : 0;   // tiles a unit computes for this request
     const int t_begin = t_off + piece * S.tiles_per_piece;
-    // lane k of a wave holds the physical page this wave fetches for tile t_begin + k (a piece has at most
-    // 60 tiles and fetches run two tiles ahead, so 64 lanes cover it).  Asked for before the lengths are
+    // lane k of a wave holds where in the pool the 16-key block lies that this wave fetches for tile t_begin + k
+    // (a piece has at most 60 tiles and fetches run two tiles ahead, so 64 lanes cover it).  Asked for before the lengths are
     // known, so that the two loads overlap: entries past the request's pages are read (the row has
     // max_pages of them) and whatever they hold is forced into the pool; those keys are masked.
     const int32_t* __restrict__ pt = b.page_table + (long long)r * b.max_pages;
-    const int pg_raw = b.max_pages > 0 ? pt[min((t_begin + lane) * 2 + (wave >> 1), b.max_pages - 1)] : 0;
+    const int blk16 = (t_begin + lane) * 2 + (wave >> 1);                 // logical 16-key block of the request
+    const int pg_raw = b.max_pages > 0 ? pt[min(blk16 >> b.page_shift, b.max_pages - 1)] : 0;
     int kv_len, n_pieces, n_rows;
     bool direct;                                             // one piece and no unit: this workgroup writes the output
     if (!unit_mode) {
@@ -128,7 +129,9 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     if (piece >= n_pieces) return;
     const int n_tiles_all = (kv_len + BK - 1) / BK;
     const int n_tiles = min(S.tiles_per_piece, n_tiles_all - t_begin);     // 0 only for an empty context
-    const int pg_vec = min(max(pg_raw, 0), b.num_pages - 1);
+    // in units of 4096 bytes (one block of one KV head): (page, KV head, block within the page)
+    const int pg_vec = ((min(max(pg_raw, 0), b.num_pages - 1) * b.num_kv_heads + kvh) << b.page_shift) +
+                       (blk16 & ((1 << b.page_shift) - 1));
     const int l32 = lane & 31, h32 = lane >> 5;
     const int limit = kv_len - 1;                            // last visible key (the query's own slot if causal)
     const int n_clear = kv_len / BK;                         // tiles 0 .. n_clear-1 need no mask
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(qp + 16 * s);
 
     // ---- global -> LDS, the prefill kernel's scheme at half the tile height: wave w brings rows 8w .. 8w+7
-    //      of the K tile and of the V tile (logical page 2 kt + w/2), K rows permuted by swap23 and both
+    //      of the K tile and of the V tile (logical 16-key block 2 kt + w/2), K rows permuted by swap23 and both
     //      with their 16-byte chunks XOR-swizzled on the source side.
     const int ld_row = lane >> 4, ld_p = lane & 15;
     const int r16 = 8 * (wave & 1) + ld_row;
@@ -153,13 +156,10 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int v_goff0 = r16 * 256 + ((ld_p ^ ((r16 & 3) << 2)) << 4);
     const unsigned char* __restrict__ kcb = (const unsigned char*)a.k_cache;
     const unsigned char* __restrict__ vcb = (const unsigned char*)a.v_cache;
-    const long long slab_bytes = (long long)b.num_kv_heads * 4096;
-    const long long head_bytes = (long long)kvh * 4096;
     const int ld_lds = wave * 8 * 256;
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
     auto load_tile = [&](int i, int slot) {                  // tile t_begin + i into ring slot `slot`
-        const int page = __builtin_amdgcn_readlane(pg_vec, i);
-        const long long off = (long long)page * slab_bytes + head_bytes;
+        const long long off = (long long)__builtin_amdgcn_readlane(pg_vec, i) * 4096;
         lds_dma16(kcb + off, k_goff0, smem_base + slot * TILE_BYTES + ld_lds);
         lds_dma16(kcb + off, (k_goff0 ^ 64) + 2048, smem_base + slot * TILE_BYTES + ld_lds + 1024);
         lds_dma16(vcb + off, v_goff0, smem_base + V_SM + slot * TILE_BYTES + ld_lds);
@@ -286,8 +286,8 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     if (FUSED && new_tile >= 0 && new_tile < n_tiles && wave == 0 && lane < 32) {
         // the token's row goes to its slot in the pool (K by lanes 0..15, V by 16..31), for the steps to come
         const int pos = kv_len - 1;
-        const int page = min(max(pt[pos >> 4], 0), b.num_pages - 1);
-        const long long dst = ((long long)page * b.num_kv_heads + kvh) * 4096 + (pos & 15) * 256 + (lane & 15) * 16;
+        const int page = min(max(pt[pos >> (4 + b.page_shift)], 0), b.num_pages - 1);
+        const long long dst = (((long long)page * b.num_kv_heads + kvh) * b.page_size + (pos & (b.page_size - 1))) * 256 + (lane & 15) * 16;
         const unsigned char* src = (const unsigned char*)(lane < 16 ? a.k_new : a.v_new) + new_row_bytes + (lane & 15) * 16;
         unsigned char* pool = (unsigned char*)const_cast<void*>(lane < 16 ? a.k_cache : a.v_cache);
         *(uint4*)(pool + dst) = *(const uint4*)src;
@@ -469,7 +469,7 @@ DecodeShape decode_shape(const BatchView& b, const SharedPrefixView& sv = Shared
     DecodeShape S;
     S.n_pairs = b.num_reqs * b.num_kv_heads;
     S.n_unit_pairs = sv.num_units * b.num_kv_heads;
-    const long long table_tiles = ((long long)b.max_pages * 16 + BK - 1) / BK;       // longest possible context
+    const long long table_tiles = ((long long)b.max_pages * b.page_size + BK - 1) / BK;       // longest possible context
     const long long own_tiles = sv.max_own_tiles > 0 ? std::min<long long>(sv.max_own_tiles, table_tiles) : table_tiles;
     const long long unit_tiles = sv.num_units == 0 ? 0
                                  : sv.max_unit_tiles > 0 ? std::min<long long>(sv.max_unit_tiles, table_tiles) : table_tiles;

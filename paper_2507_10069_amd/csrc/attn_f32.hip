@@ -52,6 +52,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
     const float* __restrict__ vc = (const float*)a.v_cache;
     const int32_t* __restrict__ pt = b.page_table + (long long)r * b.max_pages;
 
+    const int pg_log2 = 4 + b.page_shift, ps = b.page_size;
     float m = -INFINITY, l = 0.f;
     float acc[CPL];
 #pragma unroll
@@ -61,8 +62,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
         const int i = base + lane;
         float s = -INFINITY;
         if (i < len) {
-            const long long page = pt[i >> 4];
-            const float4* k4 = (const float4*)(kc + ((page * b.num_kv_heads + kvh) * 16 + (i & 15)) * D);
+            const long long page = pt[i >> pg_log2];
+            const float4* k4 = (const float4*)(kc + ((page * b.num_kv_heads + kvh) * ps + (i & (ps - 1))) * D);
             const float4* q4 = (const float4*)q;
             float dot = 0.f;
 #pragma unroll 4
@@ -85,8 +86,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
         for (int kk = 0; kk < n_here; ++kk) {
             const float pk = __shfl(p, kk);
             const int key = base + kk;
-            const long long page = pt[key >> 4];
-            const float* v = vc + ((page * b.num_kv_heads + kvh) * 16 + (key & 15)) * D;
+            const long long page = pt[key >> pg_log2];
+            const float* v = vc + ((page * b.num_kv_heads + kvh) * ps + (key & (ps - 1))) * D;
 #pragma unroll
             for (int c = 0; c < CPL; ++c) acc[c] = fmaf(pk, v[lane + 64 * c], acc[c]);
         }

@@ -15,13 +15,14 @@ struct BatchView {
     const int32_t* cu_new_lens;  // [B+1]
     int32_t num_reqs, num_q_heads, num_kv_heads, head_dim;
     int32_t page_size, num_pages, max_pages, total_new_tokens, max_new_len;
+    int32_t page_shift;          // page_size == 16 << page_shift: a page is 2^page_shift blocks of 16 tokens
     float softmax_scale;
 };
 
 struct AttnArgs {
     BatchView b;
     const void* q;        // [T][H][d]
-    const void* k_cache;  // [num_pages][Hkv][16][d]
+    const void* k_cache;  // [num_pages][Hkv][page_size][d]
     const void* v_cache;
     void* out;            // [T][H][d]
     float* lse;           // [T][H] or nullptr

@@ -32,10 +32,10 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(BatchView b, const uint
     }
     const int r = lo;
     const int pos = b.prefix_lens[r] + (t - b.cu_new_lens[r]);
-    const int page = b.page_table[(long long)r * b.max_pages + (pos >> 4)];
+    const int page = b.page_table[(long long)r * b.max_pages + (pos >> (4 + b.page_shift))];
     if (page < 0 || page >= b.num_pages) return;         // corrupt table: drop the write, never stray
 
-    const long long dst = (((long long)page * b.num_kv_heads + h) * 16 + (pos & 15)) * chunks_per_row + chunk;
+    const long long dst = (((long long)page * b.num_kv_heads + h) * b.page_size + (pos & (b.page_size - 1))) * chunks_per_row + chunk;
     k_cache[dst] = k_new[idx];
     v_cache[dst] = v_new[idx];
 }

@@ -58,7 +58,7 @@ def test_workspace_size_and_scalar_checks():
     for over in bad:
         assert lib.emm_prefill_attn_workspace_size(ctypes.byref(_batch(**over)), ctypes.byref(n)) == \
             B.EMM_ERR_INVALID_ARG, over
-    unsupported = [dict(page_size=32), dict(head_dim=64), dict(dtype="f32", head_dim=32)]
+    unsupported = [dict(page_size=8), dict(page_size=48), dict(page_size=512), dict(head_dim=64), dict(dtype="f32", head_dim=32)]
     for over in unsupported:
         assert lib.emm_prefill_attn_workspace_size(ctypes.byref(_batch(**over)), ctypes.byref(n)) == \
             B.EMM_ERR_UNSUPPORTED, over

@@ -385,6 +385,71 @@ def test_random_decode_batches(seed):
         assert bits(dw.v_cache).tobytes() == bits(ref.v_cache).tobytes()
 
 
+PAGE_SIZES = [32, 64, 128, 256]
+
+
+@pytest.mark.parametrize("ps", PAGE_SIZES)
+def test_page_sizes_prefill_and_cross(ps):
+    """Pages of 32 .. 256 tokens (a page then holds 2 .. 16 of the 16-key blocks the kernels fetch): ragged
+    lengths around page and tile edges, units cut along the keys, cross-attention, and the fp32 kernels."""
+    print("case page size", ps, "prefill", flush=True)
+    wl = W.build_workload("ps_prefill", "causal", "bf16", 6000 + ps, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                          page_size=ps, prefix_lens=[5000, 300, 0, 77, 1056, ps - 1, ps, 4 * ps + 1],
+                          new_lens=[64, 200, 150, 3, 300, 2, ps + 1, 40])
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw, _sample_tokens(wl, 96, seed=ps)), flush=True)
+    print("case page size", ps, "cut into 16 pieces", flush=True)
+    wl = W.build_workload("ps_cut16", "causal", "bf16", 6100 + ps, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                          page_size=ps, prefix_lens=[17000], new_lens=[36])
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+    print("case page size", ps, "cross", flush=True)
+    wl = W.build_workload("ps_cross", "cross", "bf16", 6200 + ps, num_q_heads=32, num_kv_heads=8, head_dim=128,
+                          page_size=ps, prefix_lens=[6404, 333, 0, 6404], new_lens=[100, 61, 5, 37],
+                          share_group=[0, 1, 2, 0], shared_len=[6404, 0, 0, 6404])
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+    print("case page size", ps, "fp32", flush=True)
+    wl = W.build_workload("ps_f32", "causal", "f32", 6300 + ps, num_q_heads=4, num_kv_heads=1, head_dim=64,
+                          page_size=ps, prefix_lens=[256, 100, 0], new_lens=[64, 3, ps + 3])
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+
+
+@pytest.mark.parametrize("ps", PAGE_SIZES)
+def test_page_sizes_decode(ps):
+    """The decode step on pages of 32 .. 256 tokens: plain, with shared-prefix units, and fused with the scatter."""
+    print("case page size", ps, "decode", flush=True)
+    bits = B.DeviceWorkload.to_numpy_bits
+    ctx = [700, 650, 900, 300, 1300, 18000, 0, ps - 1, ps, 2 * ps + 1]
+    group = [0, 0, 1, 2, 2, 3, 4, 5, 6, 7]
+    shared = [512, 512, 0, 256, 256, 0, 0, 0, 0, 0]
+
+    def build():
+        return W.build_workload("ps_decode", "causal", "bf16", 6400 + ps, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                                page_size=ps, prefix_lens=ctx, new_lens=[1] * len(ctx), share_group=group, shared_len=shared)
+    ref = _gpu_run(build())                             # scatter, then the plain decode kernels
+    print("   errors (max, mean, lse):", _compare(ref.wl, ref), flush=True)
+    plain_out = bits(ref.out).copy()
+    plan = ref.plan_shared()
+    print("   units:", plan["num_units"], plan["unit_num_reqs"].tolist(), plan["unit_shared_len"].tolist(), flush=True)
+    assert plan["num_units"] == 2 and plan["unit_shared_len"].tolist() == [512, 256]
+    ref.out.zero_()
+    ref.attention_shared()
+    torch.cuda.synchronize()
+    print("   errors (max, mean, lse):", _compare(ref.wl, ref), flush=True)
+    shared_out = bits(ref.out).copy()
+    for use_units, want in ((False, plain_out), (True, shared_out)):
+        dw = B.DeviceWorkload(build())
+        dw.plan_shared()
+        dw.out.zero_()
+        dw.decode_step(use_units)
+        torch.cuda.synchronize()
+        assert bits(dw.out).tobytes() == want.tobytes(), use_units
+        assert bits(dw.k_cache).tobytes() == bits(ref.k_cache).tobytes()
+        assert bits(dw.v_cache).tobytes() == bits(ref.v_cache).tobytes()
+
+
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     """The library only launches kernels on the given stream (no allocation, no memset, no synchronisation), so a
     step can be captured in a HIP graph; every replay, with eager work between the replays, must reproduce the
