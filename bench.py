@@ -247,6 +247,9 @@ def main():
     ap.add_argument("--decode", default=None, metavar="NAME",
                     help="time one decode-step workload instead (one query token per request; HBM-bound): "
                          "decode_video_b8, decode_mixed_b32 or decode_b64_8k")
+    ap.add_argument("--suffix", default=None, metavar="NAME",
+                    help="time one short-suffix prefill workload instead (the batch a large cache hit leaves): "
+                         "suffix_b1_16k_n36, suffix_b8_16k_n36, suffix_b8_16k_n4 or suffix_b32_4k_n36")
     ap.add_argument("--kv-migrate", action="store_true",
                     help="time the KV page migration primitive (pack and unpack with checksums) instead")
     ap.add_argument("--prefix-cache", action="store_true",
@@ -277,6 +280,31 @@ def main():
 
     if args.kv_migrate:
         return bench_kv_migrate(torch, B, args.steps, args.warmup)
+    if args.suffix is not None:
+        wl = W.suffix_config(args.suffix)
+        dw = B.DeviceWorkload(wl)
+        ms, attn_ms, scat_ms = time_workload(dw, args.steps, args.warmup)
+        tflops = wl.attention_flops() / (attn_ms * 1e-3) / 1e12
+        gbs = wl.kv_read_bytes() / (attn_ms * 1e-3) / 1e9
+        log("workload %s: %.4f ms/step (attention %.4f ms, scatter %.4f ms), %.1f TFLOP/s, %.0f GB/s of K/V read"
+            % (wl.name, ms, attn_ms, scat_ms, tflops, gbs))
+        # few rows over long contexts: neither roof is near; the one that is closer is reported
+        mfma_frac, hbm_frac = tflops / BF16_MFMA_PEAK_TFLOPS, gbs / HBM_PEAK_GBS
+        roof = ({"bound": "mfma", "achieved": tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac}
+                if mfma_frac >= hbm_frac else
+                {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac})
+        roof.update({"traffic": None, "kernel": "attn_bf16_d128_kernel + attn_bf16_merge_kernel"})
+        print(json.dumps({
+            "metric": "prefill_attention_tflops", "value": wl.attention_flops() / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+            "config": {"workload": wl.name, "requests": wl.num_reqs, "total_new_tokens": wl.total_new_tokens,
+                       "algorithmic_flops_per_step": wl.attention_flops(), "kv_read_bytes_per_step": wl.kv_read_bytes(),
+                       "parallelism": "single-gpu"},
+            "new_tokens_per_s": wl.total_new_tokens / (ms * 1e-3), "attention_ms": attn_ms, "scatter_ms": scat_ms,
+            "roofline": roof,
+        }), flush=True)
+        return
     if args.decode is not None:
         wl = W.decode_config(args.decode)
         dw = B.DeviceWorkload(wl)

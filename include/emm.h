@@ -96,7 +96,7 @@ emm_status emm_kv_scatter(const emm_batch *batch, const void *k_new, const void 
  * EMM_F32; for EMM_BF16 about 35 MB, or, for a decode batch (at most one new token per request and at most
  * 16 query heads per KV head), 8320 bytes per (request, KV head, piece), a piece being 128 to 1920 keys of the
  * longest context the page table can hold.  The bf16 kernels cut work along the key axis (prefill: the work
- * units left over after an XCD's full rounds of 32, in up to 16 pieces; decode: every context), park the pieces' accumulators
+ * units left over after an XCD's full rounds of 32, in up to 32 pieces; decode: every context), park the pieces' accumulators
  * there and merge them with a second kernel on the same stream; the contents need no initialisation and mean
  * nothing afterwards.  Calls on different streams must not share a workspace.  Host-only; reads only the
  * scalar fields. */

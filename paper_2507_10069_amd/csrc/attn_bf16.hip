@@ -94,15 +94,17 @@ __device__ inline void static_for(F&& f)
 // separate workgroups, so that the final round fills the XCD; a piece writes its unnormalised accumulator,
 // running maximum and row sum to the workspace and a second, small kernel merges the pieces of a unit.
 // An XCD with fewer units than compute units -- few requests with few new tokens each, the usual case after
-// a long cached prefix -- has nothing but a "final round": its units are cut into up to 16 pieces each, as
+// a long cached prefix -- has nothing but a "final round": its units are cut into up to 32 pieces each, as
 // many as fill the XCD, so that the latency of a long context is spread over the chip.
 // Which units are cut follows from the batch's lengths alone, so every workgroup of either kernel derives
 // the same plan by itself: no flags, counters or descriptors are exchanged.
 constexpr int CU_PER_XCD = 32;
-constexpr int MAX_PARTS = 16;                            // pieces per unit at most
+constexpr int MAX_PARTS = 32;                            // pieces per unit at most
+constexpr int MAX_SHARES = 16;                           // merge workgroups per unit at most (4 accumulator registers each)
 constexpr int PIECES_PER_XCD = CU_PER_XCD;               // tail units x pieces of an XCD never exceed its compute units
 constexpr int EXTRA_PER_XCD = CU_PER_XCD - 1;            // workgroups for pieces 1, 2, ... of an XCD's tail units
 constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
+constexpr int MIN_TILES_PER_PART_UNDERFILLED = 8;        // ... unless the compute units would stay idle otherwise
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 32;              // planning scans an XCD's pairs: keep that short
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
 
@@ -121,6 +123,7 @@ struct UnitPlan {
     int parts, part;        // the unit's key tiles are cut into `parts` ranges; this workgroup does range `part`
     int slot;               // tail slot of the unit within its XCD (meaningful when parts > 1)
     bool rows_only;         // parts == 2 stands for a halving along the rows only (never a cut along the keys)
+    int min_tiles;          // key tiles that a piece must have
 };
 
 // pieces per tail unit when rem units are left over after full_rounds rounds of 32
@@ -128,7 +131,7 @@ __host__ __device__ inline int split_factor_of(int rem, int full_rounds)
 {
     if (rem == 0) return 1;
     if (full_rounds == 0) {
-        // the whole XCD is under-filled: as many pieces per unit as fill it (1-2 units: 16, 3-4: 8, 5-8: 4, 9-16: 2)
+        // the whole XCD is under-filled: as many pieces per unit as fill it (1 unit: 32, 2: 16, 3-4: 8, 5-8: 4, 9-16: 2)
         int p = 1;
         while (p < MAX_PARTS && 2 * p * rem <= CU_PER_XCD) p *= 2;
         return p;
@@ -150,20 +153,23 @@ __host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int s
     return cnt > j ? (cnt - j + fan - 1) / fan : 0;
 }
 
-// May a unit of n_tiles key tiles be cut into `parts` pieces?  Every piece must have MIN_TILES_PER_PART
+// May a unit of n_tiles key tiles be cut into `parts` pieces?  Every piece must have min_tiles
 // tiles, and the first tile of every piece must lie wholly at or below limit_min, the last key that the
 // unit's first row sees: then each row finds a visible key in the first tile of each piece and its
 // running maximum starts finite.  (Rows only see more keys further down the tile.)
-__device__ inline bool cuttable(int n_tiles, int parts, int limit_min)
+__device__ inline bool cuttable(int n_tiles, int parts, int limit_min, int min_tiles)
 {
     const int last_begin = (parts - 1) * n_tiles / parts;
-    return n_tiles >= MIN_TILES_PER_PART * parts && (last_begin + 1) * BC - 1 <= limit_min;
+    return n_tiles >= min_tiles * parts && (last_begin + 1) * BC - 1 <= limit_min;
 }
 // Into how many pieces a unit planned for `parts` pieces is really cut: the largest power of two up to `parts`
 // that it can be cut into (1: not at all).  Every workgroup concerned with the unit finds the same number.
-__device__ inline int pieces_cut(int n_tiles, int parts, int limit_min)
+__device__ inline int pieces_cut(int n_tiles, int parts, int limit_min, int min_tiles)
 {
-    while (parts > 1 && !cuttable(n_tiles, parts, limit_min)) parts >>= 1;
+    while (parts > 1 && !cuttable(n_tiles, parts, limit_min, min_tiles)) parts >>= 1;
+    // two short pieces are no better than two row halves, which need no merge: pieces shorter than the usual
+    // minimum only when there are at least four of them
+    if (parts == 2 && !cuttable(n_tiles, 2, limit_min, MIN_TILES_PER_PART)) parts = 1;
     return parts;
 }
 
@@ -178,11 +184,11 @@ __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31
 // as many slots per pair as the longest request needs), then 31 workgroups for pieces 1, 2, ... of tail units.
 // The scan over the XCD's pairs (at most 32 when cutting is enabled) is done by the lanes of each wave.
 // merge_idx >= 0 asks instead, whatever in_xcd is, for the plan of merge workgroup merge_idx of the XCD: the unit
-// in tail slot merge_idx / parts, with .part = merge_idx % parts.
+// in tail slot merge_idx / shares, with .part = merge_idx % shares, shares = min(parts, 16).
 __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd, int merge_idx = -1)
 {
     UnitPlan u;
-    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false;
+    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false; u.min_tiles = MIN_TILES_PER_PART;
     const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
     const bool regular = merge_idx < 0 && in_xcd < n_regular;
     const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
@@ -210,6 +216,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int parts = split_factor(rem, total / CU_PER_XCD);
     if (parts == 1) return u;
     u.rows_only = rows_only_of(rem);                            // regular: whole unit; extra: nothing to do (pair < 0)
+    u.min_tiles = total < CU_PER_XCD ? MIN_TILES_PER_PART_UNDERFILLED : MIN_TILES_PER_PART;
     const int first_tail = total - rem;
     if (regular) {
         const int before_mine = __builtin_amdgcn_readfirstlane(wave_sum32(pi < my_pi ? cnt : 0));
@@ -221,7 +228,8 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
         return u;
     }
     const int e = in_xcd - n_regular;
-    const int slot = merge_idx >= 0 ? merge_idx / parts : e / (parts - 1), part = merge_idx >= 0 ? merge_idx % parts : 1 + e % (parts - 1);
+    const int shares = min(parts, MAX_SHARES);
+    const int slot = merge_idx >= 0 ? merge_idx / shares : e / (parts - 1), part = merge_idx >= 0 ? merge_idx % shares : 1 + e % (parts - 1);
     if (slot >= rem) return u;
     const int ordinal = first_tail + slot;
     // the pair that holds this ordinal: the first one whose inclusive running count exceeds it
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     int row_half = -1;                                       // -1: all eight waves work on their rows
     // into how many pieces the unit is really cut along the keys: as planned for its XCD, fewer if it is too
     // short for that, 1 if it cannot be cut at all or is only to be halved
-    const int cut = (plan.parts > 1 && !plan.rows_only) ? pieces_cut(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1) : 1;
+    const int cut = (plan.parts > 1 && !plan.rows_only) ? pieces_cut(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1, plan.min_tiles) : 1;
     if (plan.parts > 1 && cut == 1) {
         const bool halve = n_rows - row0 > BR / 2;
         if (plan.part > (halve ? 1 : 0)) return;
@@ -762,8 +770,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     }
 }
 
-// One workgroup's share of the merge of a unit planned for PARTS pieces and cut into `cut` of them: 64 / PARTS
-// of each thread's 64 accumulator registers, in groups of four (one 8-byte store each).  Every load is issued
+// One workgroup's share of the merge of a unit planned for PARTS pieces and cut into `cut` of them: one of
+// min(PARTS, 16) equal shares of each thread's 64 accumulator registers, in groups of four (one 8-byte store each).  Every load is issued
 // whatever `cut` is (pieces past the last repeat it, with weight 0) so that all of them are in flight at once.
 template <int PARTS>
 __device__ inline void merge_share(const float* __restrict__ ws0, int cut, int sub, float scale, __bf16* __restrict__ op,
@@ -791,7 +799,7 @@ __device__ inline void merge_share(const float* __restrict__ ws0, int cut, int s
         l_tot += w[j] * l_part[j];
     }
     const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
-    constexpr int N4 = 16 / PARTS;                           // groups of four registers in this share
+    constexpr int N4 = PARTS >= 16 ? 1 : 16 / PARTS;         // groups of four registers in this share (16 / shares)
     float acc[N4][4];
 #pragma unroll
     for (int i = 0; i < N4; ++i)
@@ -816,9 +824,9 @@ __device__ inline void merge_share(const float* __restrict__ ws0, int cut, int s
 }
 
 // Merges the pieces of the cut units, thread for thread the layout of the main kernel's epilogue.  An XCD
-// whose tail units are planned for p pieces each gets 32 workgroups: number k works on tail slot k / p and
-// there on share k % p of the 64 accumulator registers, so every workgroup reads the same 64 rows of 2 KB
-// whatever p is.  Workgroups whose slot holds no cut unit leave at once.
+// whose tail units are planned for p pieces each gets 32 workgroups: with s = min(p, 16) shares per unit,
+// number k works on tail slot k / s and there on share k % s of the 64 accumulator registers, so every
+// workgroup reads the same 64 rows of 2 KB whatever p is (128 rows for p = 32).  Workgroups whose slot holds no cut unit leave at once.
 __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, LaunchShape L)
 {
     const BatchView& b = a.b;
@@ -834,7 +842,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int P = b.prefix_lens[r];
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = a.causal ? P + last_row / G + 1 : P;
-    const int cut = plan.rows_only ? 1 : pieces_cut((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1);
+    const int cut = plan.rows_only ? 1 : pieces_cut((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1, plan.min_tiles);
     if (cut == 1) return;                                    // not cut along the keys
 
     const int tid = threadIdx.x;
@@ -851,7 +859,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
         case 2: merge_share<2>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
         case 4: merge_share<4>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
         case 8: merge_share<8>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        default: merge_share<16>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 16: merge_share<16>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        default: merge_share<32>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
     }
 }
 
@@ -903,7 +912,7 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     if (err != hipSuccess || !L.split) return err;
     // no context of this batch is long enough for two pieces along the keys: left-over units can only have been
     // halved along their rows, which leaves nothing to merge
-    if ((long long)b.max_pages * b.page_size < 2ll * MIN_TILES_PER_PART * BC) return err;
+    if (((long long)b.max_pages * b.page_size + BC - 1) / BC < 2ll * MIN_TILES_PER_PART) return err;
     hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * PIECES_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }

@@ -126,17 +126,20 @@ def test_ragged_cross_sweep():
 # 256-row tile of one (request, KV head) pair; pairs are dealt to the 8 XCDs; the units an XCD has left over
 # after its full rounds of 32 are cut into 4 pieces (1..8 left over) or 2 (9..12) when every piece gets at least
 # 16 key tiles and starts below the diagonal; an XCD without a full round cuts into as many pieces as fill it,
-# up to 16.
+# up to 32, of at least 8 key tiles.
 CUT_CASES = [
     # name, kind, H, Hkv, prefix lens, new lens
-    ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 1 unit per XCD, planned for 16 pieces; 80 tiles give 4
+    ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 1 unit per XCD, planned for 32 pieces; 80 tiles give 8 of 10
     ("cut2_causal", "causal", 28, 4, [2100], [350]),                # 10 units per XCD, 2 pieces each
-    ("cut4_cross", "cross", 32, 8, [6404, 6404], [100, 37]),        # 3 units per XCD, 8 planned, 4 cut; ragged last tile
-    ("cut16_causal", "causal", 28, 4, [17000], [36]),               # 1 unit on every other XCD, 267 tiles: 16 pieces
-    ("cut16_cross", "cross", 32, 8, [16500], [30]),                 # 1 unit per XCD of 120 rows, 258 tiles: 16 pieces
-    ("cut8_causal", "causal", 28, 4, [9000, 9100], [36, 20]),       # 1 unit per XCD, 142-143 tiles: 8 pieces
+    ("cut4_cross", "cross", 32, 8, [6404, 6404], [100, 37]),        # 3 units per XCD, 8 pieces; ragged last tile
+    ("cut32_causal", "causal", 28, 4, [17000], [36]),               # 1 unit on every other XCD, 267 tiles: 32 pieces
+    ("cut32_cross", "cross", 32, 8, [16500], [30]),                 # 1 unit per XCD of 120 rows, 258 tiles: 32 pieces
+    ("cut16_causal", "causal", 28, 4, [9000, 9100], [36, 20]),      # 1 unit per XCD, 142-143 tiles: 16 pieces
     ("cut8_planned", "causal", 32, 8, [8200, 8300, 9000], [50, 64, 3]),   # 3 units per XCD, 8 pieces each
-    ("cut_2units", "causal", 16, 8, [16400, 16400], [130, 7]),      # 2 and 1 units per XCD, 16 pieces each
+    ("cut_2units", "causal", 16, 8, [16400, 16400], [130, 7]),      # 2 and 1 units per XCD: 16 and 32 pieces
+    ("cut_table_edge", "causal", 28, 4, [1990, 700], [10, 3]),      # 125 pages hold 2000 slots: 32 tiles, just enough for 4 pieces
+    ("cut_table_edge2", "causal", 28, 4, [1970], [14]),             # 124 pages, 31 tiles: not cut
+    ("cut32_short", "causal", 28, 4, [16384 - 40], [40]),           # 256 tiles exactly: 32 pieces of 8, the last one on the diagonal
     ("cut_mixed", "causal", 16, 8, [8000, 100, 4100], [64, 200, 3]),  # long units are cut, short ones are not
     ("cut_edge", "causal", 8, 8, [4091, 4096, 4000, 1800], [5, 5, 200, 300]),  # 64 tiles: just cut; 63: not cut;
                                                                     # a last piece that would start on the diagonal
