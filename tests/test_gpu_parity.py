@@ -170,6 +170,23 @@ def test_cut_units_parity(name, kind, H, Hkv, prefix, new):
     assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
 
 
+@pytest.mark.parametrize("kind,n_req", [("causal", 1), ("causal", 2), ("cross", 1), ("cross", 3)])
+def test_cut_thresholds_sweep(kind, n_req):
+    """Contexts whose key-tile counts sit on and around every threshold of the cutting rule (pieces of at least
+    8 or 16 tiles, 2 .. 32 of them), with the page table exactly as wide as the context needs: one and two
+    requests, so that an XCD holds one unit (32 pieces planned) or two (16); three for cross-attention (8)."""
+    for tiles in (15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257):
+        for slack in (0, 1, 63):                           # the last tile full, one key short, one key only
+            ctx = tiles * 64 - slack
+            new = 3
+            print("case thresholds", n_req, tiles, slack, flush=True)
+            wl = W.build_workload("thresholds", kind, "bf16", 7000 + tiles, num_q_heads=8, num_kv_heads=4,
+                                  head_dim=128, page_size=16, prefix_lens=[ctx - new if kind == "causal" else ctx] * n_req,
+                                  new_lens=[new] * n_req, spare_pages=0)
+            dw = _gpu_run(wl)
+            _compare(wl, dw)
+
+
 @pytest.mark.parametrize("H,Hkv,prefix,new", [(4, 1, [300], [700]), (8, 2, [0], [1500]), (6, 1, [70, 0, 513], [300, 90, 64]),
                                               (8, 4, [129], [1]), (2, 1, [5000], [1100])])
 def test_few_pairs_spread_over_xcds(H, Hkv, prefix, new):
