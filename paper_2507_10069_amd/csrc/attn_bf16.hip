@@ -141,10 +141,12 @@ __host__ __device__ inline int split_factor_of(int rem, int full_rounds)
     if (rem > 12) return 1;
     return rem > 8 ? 2 : 4;
 }
-// 13 .. 16 leftover units are not cut along the keys (see above) but still halved along their rows: the 26 .. 32
-// halves fill the XCD's last round, cost nothing to merge, and each finishes in about 60 % of a unit's time
-__host__ __device__ inline bool rows_only_of(int rem) { return rem > 12 && rem <= CU_PER_XCD / 2; }
-__host__ __device__ inline int split_factor(int rem, int full_rounds) { return rows_only_of(rem) ? 2 : split_factor_of(rem, full_rounds); }
+// 13 .. 16 units left over after full rounds are not cut along the keys (see above) but still halved along their
+// rows: the 26 .. 32 halves fill the XCD's last round, cost nothing to merge, and each finishes in about 60 % of
+// a unit's time.  (On an XCD without a full round they are cut in two along the keys, which also helps units
+// of few rows, where there is nothing to halve.)
+__host__ __device__ inline bool rows_only_of(int rem, int full_rounds) { return full_rounds > 0 && rem > 12 && rem <= CU_PER_XCD / 2; }
+__host__ __device__ inline int split_factor(int rem, int full_rounds) { return rows_only_of(rem, full_rounds) ? 2 : split_factor_of(rem, full_rounds); }
 
 // row tiles (units) of sub-pair sp
 __host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int sp)
@@ -215,7 +217,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int rem = total % CU_PER_XCD;
     const int parts = split_factor(rem, total / CU_PER_XCD);
     if (parts == 1) return u;
-    u.rows_only = rows_only_of(rem);                            // regular: whole unit; extra: nothing to do (pair < 0)
+    u.rows_only = rows_only_of(rem, total / CU_PER_XCD);                            // regular: whole unit; extra: nothing to do (pair < 0)
     u.min_tiles = total < CU_PER_XCD ? MIN_TILES_PER_PART_UNDERFILLED : MIN_TILES_PER_PART;
     const int first_tail = total - rem;
     if (regular) {
