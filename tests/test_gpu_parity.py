@@ -149,8 +149,9 @@ CUT_CASES = [
     ("halve_one", "causal", 28, 4, [700], [36]),                    # 252 rows: one unit per head, halved
     ("halve_small", "causal", 28, 4, [700, 50], [18, 19]),          # 126 and 133 rows: nothing to halve / halved
     ("halve_cross", "cross", 32, 8, [900, 333], [60, 61]),          # 240 and 244 rows, no mask
-    ("halve_14", "causal", 56, 8, [100], [512]),                    # 14 units per XCD: rows only, short context
-    ("halve_14_long", "causal", 56, 8, [9000], [512]),              # 14 units per XCD, long context: still rows only
+    ("halve_14", "causal", 56, 8, [100], [512]),                    # 14 units per XCD, short context: halved
+    ("halve_14_long", "causal", 56, 8, [9000], [512]),              # 14 units per XCD, long context: two pieces along the keys
+    ("halve_46_long", "causal", 56, 8, [9000], [1670]),             # 46 units per XCD = a full round + 14: those are halved, never cut
     ("halve_ragged", "causal", 28, 4, [300, 1056, 0, 77], [100, 37, 150, 3]),   # last row tiles of 188, 3, 26, 21 rows
 ]
 
