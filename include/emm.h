@@ -93,7 +93,7 @@ emm_status emm_kv_scatter(const emm_batch *batch, const void *k_new, const void 
                           void *k_cache, void *v_cache, void *hip_stream);
 
 /* Bytes of device workspace emm_prefill_attn / emm_cross_attn / emm_decode_attn need for this batch: 0 for
- * EMM_F32; for EMM_BF16 about 35 MB, or, for a decode batch (at most one new token per request and at most
+ * EMM_F32; for EMM_BF16 about 69 MB, or, for a decode batch (at most one new token per request and at most
  * 16 query heads per KV head), 8320 bytes per (request, KV head, piece), a piece being 128 to 1920 keys of the
  * longest context the page table can hold.  The bf16 kernels cut work along the key axis (prefill: the work
  * units left over after an XCD's full rounds of 32, in up to 32 pieces; decode: every context), park the pieces' accumulators

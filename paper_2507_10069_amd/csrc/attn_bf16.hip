@@ -100,8 +100,7 @@ __device__ inline void static_for(F&& f)
 // the same plan by itself: no flags, counters or descriptors are exchanged.
 constexpr int CU_PER_XCD = 32;
 constexpr int MAX_PARTS = 32;                            // pieces per unit at most
-constexpr int MAX_SHARES = 16;                           // merge workgroups per unit at most (4 accumulator registers each)
-constexpr int PIECES_PER_XCD = CU_PER_XCD;               // tail units x pieces of an XCD never exceed its compute units
+constexpr int PIECES_PER_XCD = 2 * CU_PER_XCD;           // tail units x pieces of an XCD: at most 32, or 2 x 30 (uneven cuts)
 constexpr int EXTRA_PER_XCD = CU_PER_XCD - 1;            // workgroups for pieces 1, 2, ... of an XCD's tail units
 constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
 constexpr int MIN_TILES_PER_PART_UNDERFILLED = 8;        // ... unless the compute units would stay idle otherwise
@@ -116,6 +115,7 @@ struct LaunchShape {
     int pairs_per_xcd;      // ceil(n_pairs / 8)
     int split;              // 1: tail units may be cut (workspace present)
     int fan;                // sub-pairs per (request, KV head) pair: 1, 2, 4 or 8
+    int uneven;             // 1: 17 .. 30 units in an XCD's last round are cut unevenly (see uneven_of)
 };
 
 struct UnitPlan {
@@ -124,6 +124,7 @@ struct UnitPlan {
     int slot;               // tail slot of the unit within its XCD (meaningful when parts > 1)
     bool rows_only;         // parts == 2 stands for a halving along the rows only (never a cut along the keys)
     int min_tiles;          // key tiles that a piece must have
+    int uneven;             // > 0: parts == 2 and piece 0 gets uneven / (uneven + 1) of the key tiles (see uneven_of)
 };
 
 // pieces per tail unit when rem units are left over after full_rounds rounds of 32
@@ -146,7 +147,18 @@ __host__ __device__ inline int split_factor_of(int rem, int full_rounds)
 // a unit's time.  (On an XCD without a full round they are cut in two along the keys, which also helps units
 // of few rows, where there is nothing to halve.)
 __host__ __device__ inline bool rows_only_of(int rem, int full_rounds) { return full_rounds > 0 && rem > 12 && rem <= CU_PER_XCD / 2; }
-__host__ __device__ inline int split_factor(int rem, int full_rounds) { return rows_only_of(rem, full_rounds) ? 2 : split_factor_of(rem, full_rounds); }
+// 17 .. 30 units in the last round leave 15 .. 2 compute units idle for a whole unit's time.  Each of those units is
+// cut in two UNEVEN pieces: the long ones keep rem compute units busy, the short ones are dealt k to each of the
+// 32 - rem others, k = ceil(rem / (32 - rem)); with the cut at k / (k + 1) of the keys both kinds finish together,
+// after k / (k + 1) of a unit's time instead of 1 (24 units: k = 3, cut at 3/4).  Returns k, or 0 if rem is not in range.
+__host__ __device__ inline int uneven_of(int rem)
+{
+    return (rem > CU_PER_XCD / 2 && rem <= CU_PER_XCD - 2) ? (rem + (CU_PER_XCD - rem) - 1) / (CU_PER_XCD - rem) : 0;
+}
+__host__ __device__ inline int split_factor(int rem, int full_rounds, int uneven_ok)
+{
+    return (rows_only_of(rem, full_rounds) || (uneven_ok && uneven_of(rem) > 0)) ? 2 : split_factor_of(rem, full_rounds);
+}
 
 // row tiles (units) of sub-pair sp
 __host__ __device__ inline int sub_pair_tiles(int new_len, int G, int fan, int sp)
@@ -174,6 +186,14 @@ __device__ inline int pieces_cut(int n_tiles, int parts, int limit_min, int min_
     if (parts == 2 && !cuttable(n_tiles, 2, limit_min, MIN_TILES_PER_PART)) parts = 1;
     return parts;
 }
+// first tile of piece 1 of a unit cut unevenly, k short pieces to a compute unit
+__device__ inline int uneven_split(int n_tiles, int k) { return n_tiles * k / (k + 1); }
+// may it be cut that way?  (the same two conditions as in cuttable, for the short piece)
+__device__ inline bool uneven_cuttable(int n_tiles, int k, int limit_min)
+{
+    const int split = uneven_split(n_tiles, k);
+    return n_tiles - split >= MIN_TILES_PER_PART && (split + 1) * BC - 1 <= limit_min;
+}
 
 __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31 (and, separately, 32..63)
 {
@@ -186,11 +206,11 @@ __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31
 // as many slots per pair as the longest request needs), then 31 workgroups for pieces 1, 2, ... of tail units.
 // The scan over the XCD's pairs (at most 32 when cutting is enabled) is done by the lanes of each wave.
 // merge_idx >= 0 asks instead, whatever in_xcd is, for the plan of merge workgroup merge_idx of the XCD: the unit
-// in tail slot merge_idx / shares, with .part = merge_idx % shares, shares = min(parts, 16).
+// in tail slot merge_idx / shares, with .part = merge_idx % shares, shares = parts (1 for an uneven cut).
 __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd, int merge_idx = -1)
 {
     UnitPlan u;
-    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false; u.min_tiles = MIN_TILES_PER_PART;
+    u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false; u.min_tiles = MIN_TILES_PER_PART; u.uneven = 0;
     const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
     const bool regular = merge_idx < 0 && in_xcd < n_regular;
     const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
@@ -215,10 +235,11 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
                         ? sub_pair_tiles(b.new_lens[lane_sp / L.fan / b.num_kv_heads], G, L.fan, lane_sp) : 0;
     const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
     const int rem = total % CU_PER_XCD;
-    const int parts = split_factor(rem, total / CU_PER_XCD);
+    const int parts = split_factor(rem, total / CU_PER_XCD, L.uneven);
     if (parts == 1) return u;
     u.rows_only = rows_only_of(rem, total / CU_PER_XCD);                            // regular: whole unit; extra: nothing to do (pair < 0)
     u.min_tiles = total < CU_PER_XCD ? MIN_TILES_PER_PART_UNDERFILLED : MIN_TILES_PER_PART;
+    u.uneven = L.uneven ? uneven_of(rem) : 0;
     const int first_tail = total - rem;
     if (regular) {
         const int before_mine = __builtin_amdgcn_readfirstlane(wave_sum32(pi < my_pi ? cnt : 0));
@@ -230,7 +251,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
         return u;
     }
     const int e = in_xcd - n_regular;
-    const int shares = min(parts, MAX_SHARES);
+    const int shares = u.uneven > 0 ? 1 : parts;             // merge workgroups per unit
     const int slot = merge_idx >= 0 ? merge_idx / shares : e / (parts - 1), part = merge_idx >= 0 ? merge_idx % shares : 1 + e % (parts - 1);
     if (slot >= rem) return u;
     const int ordinal = first_tail + slot;
@@ -297,8 +318,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     int row_half = -1;                                       // -1: all eight waves work on their rows
     // into how many pieces the unit is really cut along the keys: as planned for its XCD, fewer if it is too
     // short for that, 1 if it cannot be cut at all or is only to be halved
-    const int cut = (plan.parts > 1 && !plan.rows_only) ? pieces_cut(n_tiles_unit, plan.parts, CAUSAL ? P + row0 / G : P - 1, plan.min_tiles) : 1;
-    if (plan.parts > 1 && cut == 1) {
+    const int limit_first_row = CAUSAL ? P + row0 / G : P - 1;
+    const int cut = (plan.parts == 1 || plan.rows_only) ? 1
+                    : plan.uneven > 0 ? (uneven_cuttable(n_tiles_unit, plan.uneven, limit_first_row) ? 2 : 1)
+                                      : pieces_cut(n_tiles_unit, plan.parts, limit_first_row, plan.min_tiles);
+    if (plan.uneven > 0 && cut == 1) {
+        if (plan.part > 0) return;                           // too short to cut: the regular workgroup does it all
+    } else if (plan.parts > 1 && cut == 1) {
         const bool halve = n_rows - row0 > BR / 2;
         if (plan.part > (halve ? 1 : 0)) return;
         if (halve) row_half = plan.part;
@@ -307,8 +333,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         return;
     }
     // this workgroup's key tiles: t_begin .. t_begin + n_tiles - 1
-    const int t_begin = plan.part * n_tiles_unit / cut;
-    const int n_tiles = (plan.part + 1) * n_tiles_unit / cut - t_begin;
+    const int t_split = uneven_split(n_tiles_unit, plan.uneven);          // meaningful for an uneven cut only
+    const int t_begin = (plan.uneven > 0 && cut == 2) ? (plan.part ? t_split : 0) : plan.part * n_tiles_unit / cut;
+    const int n_tiles = (plan.uneven > 0 && cut == 2) ? (plan.part ? n_tiles_unit - t_split : t_split)
+                                                      : (plan.part + 1) * n_tiles_unit / cut - t_begin;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -772,63 +800,65 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     }
 }
 
-// One workgroup's share of the merge of a unit planned for PARTS pieces and cut into `cut` of them: one of
-// min(PARTS, 16) equal shares of each thread's 64 accumulator registers, in groups of four (one 8-byte store each).  Every load is issued
-// whatever `cut` is (pieces past the last repeat it, with weight 0) so that all of them are in flight at once.
-template <int PARTS>
-__device__ inline void merge_share(const float* __restrict__ ws0, int cut, int sub, float scale, __bf16* __restrict__ op,
-                                   int h32, float* __restrict__ lse)
+// One workgroup's share of the merge of a unit planned for PARTS pieces and cut into `cut` of them: REGS = 64 / SHARES
+// consecutive ones of each thread's 64 accumulator registers (32 pieces: 32 shares of 2 registers, so that what is
+// in flight fits the register file).  Every load is issued whatever `cut` is (pieces past the last repeat it,
+// with weight 0), all of them before the first use, so that one memory latency covers them.
+template <int PARTS, int SHARES = PARTS>
+__device__ inline void merge_share(const float* __restrict__ ws0, unsigned tid, int cut, int sub, float scale,
+                                   __bf16* __restrict__ op, int h32, float* __restrict__ lse)
 {
+    // ws0 is the same for the whole workgroup and tid a 32-bit offset: loads with a scalar base, no address registers
     const float c_log2 = scale * 1.44269504088896340736f;
-    float m_part[PARTS], l_part[PARTS], w[PARTS];
-    size_t off[PARTS];
+    constexpr int REGS = 64 / SHARES;
+    float m_part[PARTS], l_part[PARTS], val[PARTS][REGS];
+#pragma unroll
+    for (int j = 0; j < PARTS; ++j) {
+        const float* __restrict__ wsj = ws0 + (size_t)min(j, cut - 1) * PART_FLOATS;
+        m_part[j] = (wsj + 64 * NTHREADS)[tid];
+        l_part[j] = (wsj + 65 * NTHREADS)[tid];
+#pragma unroll
+        for (int i = 0; i < REGS; ++i) val[j][i] = (wsj + (size_t)(sub * REGS + i) * NTHREADS)[tid];
+    }
     float m_all = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < PARTS; ++j) {
-        off[j] = (size_t)min(j, cut - 1) * PART_FLOATS;
-        m_part[j] = ws0[off[j] + 64 * NTHREADS];
-        l_part[j] = ws0[off[j] + 65 * NTHREADS];
-    }
+    for (int j = 0; j < PARTS; ++j)
+        if (j < cut) m_all = fmaxf(m_all, m_part[j]);
+    float l_tot = 0.f, acc[REGS];
+#pragma unroll
+    for (int i = 0; i < REGS; ++i) acc[i] = 0.f;
 #pragma unroll
     for (int j = 0; j < PARTS; ++j) {
-        if (j >= cut) m_part[j] = -INFINITY;
-        m_all = fmaxf(m_all, m_part[j]);
-    }
-    float l_tot = 0.f;
+        const float w = j < cut ? __builtin_amdgcn_exp2f((m_part[j] - m_all) * c_log2) : 0.f;
+        l_tot += w * l_part[j];
 #pragma unroll
-    for (int j = 0; j < PARTS; ++j) {
-        w[j] = __builtin_amdgcn_exp2f((m_part[j] - m_all) * c_log2);
-        l_tot += w[j] * l_part[j];
+        for (int i = 0; i < REGS; ++i) acc[i] += w * val[j][i];
     }
     const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
-    constexpr int N4 = PARTS >= 16 ? 1 : 16 / PARTS;         // groups of four registers in this share (16 / shares)
-    float acc[N4][4];
+    // register 4g + e of a thread is channel 32 (g / 4) + 8 (g % 4) + 4 h32 + e
+    if constexpr (REGS == 2) {
+        const int g = sub >> 1;
+        bf16x2 o;
+        o[0] = (__bf16)(acc[0] * inv);
+        o[1] = (__bf16)(acc[1] * inv);
+        *(bf16x2*)(op + 32 * (g >> 2) + 8 * (g & 3) + 4 * h32 + 2 * (sub & 1)) = o;
+    } else {
 #pragma unroll
-    for (int i = 0; i < N4; ++i)
+        for (int i = 0; i < REGS / 4; ++i) {
+            const int g = sub * (REGS / 4) + i;
+            bf16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
-#pragma unroll
-    for (int j = 0; j < PARTS; ++j)
-#pragma unroll
-        for (int i = 0; i < N4; ++i)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[i][e] += w[j] * ws0[off[j] + (size_t)(4 * (sub * N4 + i) + e) * NTHREADS];
-#pragma unroll
-    for (int i = 0; i < N4; ++i) {
-        // registers 4g .. 4g+3 of a thread are channels 32 (g / 4) + 8 (g % 4) + 4 h32 + 0..3
-        const int g = sub * N4 + i;
-        bf16x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[i][e] * inv);
-        *(bf16x4*)(op + 32 * (g >> 2) + 8 * (g & 3) + 4 * h32) = o;
+            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[4 * i + e] * inv);
+            *(bf16x4*)(op + 32 * (g >> 2) + 8 * (g & 3) + 4 * h32) = o;
+        }
     }
     if (lse != nullptr) *lse = (l_tot > 0.f) ? m_all * scale + logf(l_tot) : -INFINITY;
 }
 
 // Merges the pieces of the cut units, thread for thread the layout of the main kernel's epilogue.  An XCD
-// whose tail units are planned for p pieces each gets 32 workgroups: with s = min(p, 16) shares per unit,
-// number k works on tail slot k / s and there on share k % s of the 64 accumulator registers, so every
-// workgroup reads the same 64 rows of 2 KB whatever p is (128 rows for p = 32).  Workgroups whose slot holds no cut unit leave at once.
+// whose tail units are planned for p pieces each gets 32 workgroups: number k works on tail slot k / p and
+// there on share k % p of the 64 accumulator registers, so every workgroup reads the same 64 rows of 2 KB
+// whatever p is (one workgroup per unit, 128 rows, for an uneven cut in two).  Workgroups whose slot holds no cut unit leave at once.
 __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, LaunchShape L)
 {
     const BatchView& b = a.b;
@@ -844,7 +874,10 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int P = b.prefix_lens[r];
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = a.causal ? P + last_row / G + 1 : P;
-    const int cut = plan.rows_only ? 1 : pieces_cut((kv_len + BC - 1) / BC, plan.parts, a.causal ? P + row0 / G : P - 1, plan.min_tiles);
+    const int limit_first_row = a.causal ? P + row0 / G : P - 1;
+    const int cut = plan.rows_only ? 1
+                    : plan.uneven > 0 ? (uneven_cuttable((kv_len + BC - 1) / BC, plan.uneven, limit_first_row) ? 2 : 1)
+                                      : pieces_cut((kv_len + BC - 1) / BC, plan.parts, limit_first_row, plan.min_tiles);
     if (cut == 1) return;                                    // not cut along the keys
 
     const int tid = threadIdx.x;
@@ -854,15 +887,19 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int tok = row / G;
     const int hq = kvh * G + (row - tok * G);
     const long long q_row = (long long)b.cu_new_lens[r] + tok;
-    const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, plan.parts, 0) + tid;
+    const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, plan.parts, 0);
     __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
     float* lse = (a.lse != nullptr && h32 == 0 && plan.part == 0) ? a.lse + q_row * b.num_q_heads + hq : nullptr;
+    if (plan.uneven > 0) {
+        merge_share<2, 1>(ws0, tid, cut, 0, b.softmax_scale, op, h32, lse);
+        return;
+    }
     switch (plan.parts) {
-        case 2: merge_share<2>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        case 4: merge_share<4>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        case 8: merge_share<8>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        case 16: merge_share<16>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        default: merge_share<32>(ws0, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 2: merge_share<2>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 4: merge_share<4>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 8: merge_share<8>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 16: merge_share<16>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        default: merge_share<32>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
     }
 }
 
@@ -892,15 +929,25 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     L.pairs_per_xcd = (int)pairs_per_xcd;
     L.fan = fan;
     L.split = (a.workspace != nullptr && pairs_per_xcd <= SPLIT_MAX_PAIRS_PER_XCD) ? 1 : 0;
+    L.uneven = 1;
     if (L.split && (long long)b.num_reqs * b.max_new_len == b.total_new_tokens) {
         // every request has max_new_len new tokens, so the host knows each XCD's unit count and can tell
         // whether any tail unit would be cut at all; if none, the extra workgroups and the merge launch go
-        bool any = false;
+        long long units[NUM_XCD];
+        bool alike = true;
         for (int x = 0; x < NUM_XCD; ++x) {
-            long long units = 0;
-            for (long long sp = x; sp < n_pairs; sp += NUM_XCD) units += sub_pair_tiles(b.max_new_len, G, fan, (int)sp);
-            any = any || split_factor((int)(units % CU_PER_XCD), (int)(units / CU_PER_XCD)) > 1;
+            units[x] = 0;
+            for (long long sp = x; sp < n_pairs; sp += NUM_XCD) units[x] += sub_pair_tiles(b.max_new_len, G, fan, (int)sp);
+            alike = alike && units[x] == units[0];
         }
+        // Uneven cuts shorten the last round of an XCD.  When every XCD has the same number of units, all of them
+        // are in their last round together, and the chip being power limited, the compute units that run then use
+        // the budget of those that idle: measured, the cut gains nothing there and the merge costs 2 %.  It pays
+        // when XCDs finish at different times (ragged batches: 4 % on the cross-attention workload).
+        if (alike) L.uneven = 0;
+        bool any = false;
+        for (int x = 0; x < NUM_XCD; ++x)
+            any = any || split_factor((int)(units[x] % CU_PER_XCD), (int)(units[x] / CU_PER_XCD), L.uneven) > 1;
         if (!any) L.split = 0;
     }
     const long long per_xcd = pairs_per_xcd * n_row_tiles + (L.split ? EXTRA_PER_XCD : 0);

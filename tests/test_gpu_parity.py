@@ -152,6 +152,13 @@ CUT_CASES = [
     ("halve_14", "causal", 56, 8, [100], [512]),                    # 14 units per XCD, short context: halved
     ("halve_14_long", "causal", 56, 8, [9000], [512]),              # 14 units per XCD, long context: two pieces along the keys
     ("halve_46_long", "causal", 56, 8, [9000], [1670]),             # 46 units per XCD = a full round + 14: those are halved, never cut
+    # 17 .. 30 units in an XCD's last round: each cut in two uneven pieces (k short ones per otherwise idle compute unit)
+    ("uneven_25", "causal", 28, 4, [6000, 6100], [878, 870]),       # 25 units per XCD: k = 4, cut at 4/5 of 108+ tiles
+    ("uneven_17", "causal", 32, 8, [4000], [1088]),                 # 17 units per XCD: k = 2, cut at 2/3
+    ("uneven_30", "causal", 32, 8, [17000], [1920]),                # 30 units per XCD: k = 15, short pieces of 16-18 tiles
+    ("uneven_short", "causal", 28, 4, [500, 520], [878, 878]),      # 25 units per XCD, too short to cut: whole units
+    ("uneven_cross", "cross", 32, 8, [9000], [1088]),               # 17 units per XCD, no mask
+    ("uneven_after_round", "causal", 56, 8, [5000], [2100]),        # 58 units per XCD = a full round + 26: k = 5
     ("halve_ragged", "causal", 28, 4, [300, 1056, 0, 77], [100, 37, 150, 3]),   # last row tiles of 188, 3, 26, 21 rows
 ]
 
