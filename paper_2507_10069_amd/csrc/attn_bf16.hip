@@ -90,7 +90,8 @@ __device__ inline void static_for(F&& f)
 // ---- Work units, and cutting the last ones along the key axis.
 // A unit is one row tile of one (request, KV head) pair.  An XCD works through its units in launch order on
 // its 32 compute units, so with U units the last U mod 32 of them run in a final, partly empty round.  When
-// a workspace is given, each of those tail units is cut into 2 or 4 pieces of equal key range, done by
+// a workspace is given, each of those tail units is cut into 2 or 4 pieces of equal key range (1 .. 12 units),
+// halved along its rows (13 .. 16) or cut into a long and a short piece (17 .. 30), done by
 // separate workgroups, so that the final round fills the XCD; a piece writes its unnormalised accumulator,
 // running maximum and row sum to the workspace and a second, small kernel merges the pieces of a unit.
 // An XCD with fewer units than compute units -- few requests with few new tokens each, the usual case after
