@@ -104,6 +104,20 @@ class Workload:
                 total += p + (n if self.kind == "causal" else 0)
         return 2 * total * self.num_kv_heads * self.head_dim * self.elt_bytes
 
+    def kv_distinct_read_bytes(self) -> int:
+        """As kv_read_bytes, but a physical page that several requests reference counts once (with the most
+        slots any of them sees in it): what HBM has to deliver at least when shared pages are read once."""
+        ps = self.page_size
+        seen = {}
+        for r, (p, n) in enumerate(zip(self.prefix_lens.tolist(), self.new_lens.tolist())):
+            if n <= 0:
+                continue
+            ctx = p + (n if self.kind == "causal" else 0)
+            for lp in range(-(-ctx // ps)):
+                page = int(self.page_table[r, lp])
+                seen[page] = max(seen.get(page, 0), min(ps, ctx - lp * ps))
+        return 2 * sum(seen.values()) * self.num_kv_heads * self.head_dim * self.elt_bytes
+
     def scatter_bytes(self) -> int:
         """Bytes the KV scatter must move: read K,V of the new tokens and write them once."""
         if self.kind != "causal":
