@@ -78,3 +78,12 @@ def test_config5_cross_pairs():
     # the last page holds 4 valid tokens and 12 sentinel slots
     last = wl.k_cache[wl.page_table[0, 400]]
     assert (last[:, 4:, :] == W.SENTINEL_BF16_BITS).all() and not (last[:, :4, :] == W.SENTINEL_BF16_BITS).all()
+
+
+def test_distinct_kv_bytes_count_shared_pages_once():
+    plain = W.decode_config("decode_video_b8", 16)
+    assert plain.kv_distinct_read_bytes() == plain.kv_read_bytes()
+    shared = W.decode_config("decode_shared_video_b8", 16)          # 8 requests, 1024 shared + 128 own tokens + the new one
+    per_token = 2 * shared.num_kv_heads * shared.head_dim * shared.elt_bytes
+    assert shared.kv_read_bytes() == 8 * (1024 + 128 + 1) * per_token
+    assert shared.kv_distinct_read_bytes() == (1024 + 8 * (128 + 1)) * per_token
