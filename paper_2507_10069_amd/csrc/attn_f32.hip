@@ -61,12 +61,13 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
     for (int base = 0; base < len; base += 64) {
         const int i = base + lane;
         float s = -INFINITY;
+        int my_page = 0;                                 // page of key base + lane; the value phase gets it by shuffle
         if (i < len) {
-            const long long page = pt[i >> pg_log2];
+            const long long page = my_page = pt[i >> pg_log2];
             const float4* k4 = (const float4*)(kc + ((page * b.num_kv_heads + kvh) * ps + (i & (ps - 1))) * D);
             const float4* q4 = (const float4*)q;
             float dot = 0.f;
-#pragma unroll 4
+#pragma unroll 16
             for (int c = 0; c < D / 4; ++c) {
                 const float4 kv = k4[c], qv = q4[c];
                 dot = fmaf(qv.x, kv.x, dot);
@@ -83,13 +84,25 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
 #pragma unroll
         for (int c = 0; c < CPL; ++c) acc[c] *= alpha;
         const int n_here = min(64, len - base);
-        for (int kk = 0; kk < n_here; ++kk) {
-            const float pk = __shfl(p, kk);
-            const int key = base + kk;
-            const long long page = pt[key >> pg_log2];
-            const float* v = vc + ((page * b.num_kv_heads + kvh) * ps + (key & (ps - 1))) * D;
+        // sixteen keys at a time: their V rows are all requested before the first is used (the page of key
+        // base + kk comes from lane kk by shuffle, so no load sits in the chain that leads to a row's address);
+        // keys past the chunk's end repeat its last key with weight 0
+        constexpr int GROUP = 16;
+        for (int kk0 = 0; kk0 < n_here; kk0 += GROUP) {
+            float pk[GROUP], vv[GROUP][CPL];
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) acc[c] = fmaf(pk, v[lane + 64 * c], acc[c]);
+            for (int u = 0; u < GROUP; ++u) {
+                const int kk = min(kk0 + u, n_here - 1);
+                pk[u] = kk0 + u < n_here ? __shfl(p, kk) : 0.f;
+                const long long page = __shfl(my_page, kk);
+                const float* v = vc + ((page * b.num_kv_heads + kvh) * ps + ((base + kk) & (ps - 1))) * D;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) vv[u][c] = v[lane + 64 * c];
+            }
+#pragma unroll
+            for (int u = 0; u < GROUP; ++u)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) acc[c] = fmaf(pk[u], vv[u][c], acc[c]);
         }
         m = m_new;
     }
