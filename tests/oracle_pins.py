@@ -48,6 +48,17 @@ def pin_dense_recompute_sweep(lib):
                 _dense_case(rng, P, N, ps, H, Hkv, d, dtype, lib)
 
 
+def pin_dense_recompute_large_pages(lib):
+    """The same identity with pages of 32 and 64 tokens (the device kernels take pages up to 256): prefixes and
+    suffixes that end inside, at and just past a page."""
+    rng = np.random.default_rng(14)
+    for P in (0, 31, 32, 65, 130):
+        for N in (1, 33, 70):
+            for ps in (32, 64):
+                H, Hkv = ((4, 1), (4, 2), (6, 3))[(P + N + ps) % 3]
+                _dense_case(rng, P, N, ps, H, Hkv, 8, ("f32", "bf16")[(P + N) % 2], lib)
+
+
 def pin_dense_recompute_gqa(lib):
     """Head grouping with several KV heads and a group size that is not a power of two."""
     rng = np.random.default_rng(12)
@@ -263,6 +274,6 @@ def pin_weights_sum_to_one(lib):
             np.testing.assert_allclose(out[j, h], w @ v[:P + j + 1, h // 2].astype(np.float64), rtol=0, atol=1e-13)
 
 
-ALL_PINS = [pin_dense_recompute_sweep, pin_dense_recompute_gqa, pin_dense_recompute_batch, pin_cross_dense,
+ALL_PINS = [pin_dense_recompute_sweep, pin_dense_recompute_large_pages, pin_dense_recompute_gqa, pin_dense_recompute_batch, pin_cross_dense,
             pin_closed_forms, pin_golden_causal, pin_golden_gqa, pin_golden_cross, pin_scipy_page_size_one,
             pin_scatter_bytes, pin_weights_sum_to_one]
