@@ -203,30 +203,30 @@ __device__ inline int wave_sum32(int x)                  // sum over lanes 0..31
     return x;
 }
 
-// Plan of workgroup `in_xcd` of XCD `xcd`.  Regular workgroups come first (pair-major, row tiles descending,
-// as many slots per pair as the longest request needs), then 31 workgroups for pieces 1, 2, ... of tail units.
-// The scan over the XCD's pairs (at most 32 when cutting is enabled) is done by the lanes of each wave.
+// Plan of workgroup `in_xcd` of XCD `xcd`.
+// Without cutting (L.split == 0: no workspace, or more than 32 pairs on an XCD) the grid has as many slots per
+// pair as the longest request needs (pair-major, row tiles descending) and a workgroup whose slot holds no
+// row tile leaves at once.
+// With cutting, the lanes of each wave scan the XCD's pairs (at most 32), which gives every workgroup the number
+// of units of its XCD and of every pair before it.  Workgroup j then takes unit j in the same order (pair-major,
+// row tiles descending); the workgroups after the last unit do pieces 1, 2, ... of the tail units; what is left
+// of the grid (sized for the longest request) has nothing to do.  All empty workgroups thus lie at the end of
+// the grid: the dispatcher hands out workgroups in order and waits when the next one does not fit anywhere,
+// so empty ones in between real ones (a batch of one long request and many short ones) would hold those up.
 // merge_idx >= 0 asks instead, whatever in_xcd is, for the plan of merge workgroup merge_idx of the XCD: the unit
 // in tail slot merge_idx / shares, with .part = merge_idx % shares, shares = parts (1 for an uneven cut).
 __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShape& L, int xcd, int in_xcd, int merge_idx = -1)
 {
     UnitPlan u;
     u.pair = -1; u.tile = 0; u.parts = 1; u.part = 0; u.slot = 0; u.rows_only = false; u.min_tiles = MIN_TILES_PER_PART; u.uneven = 0;
-    const int n_regular = L.pairs_per_xcd * L.n_row_tiles;
-    const bool regular = merge_idx < 0 && in_xcd < n_regular;
-    const int my_pi = in_xcd / L.n_row_tiles;            // only meaningful for regular workgroups
-    int my_cnt = 0, my_idx = 0;
-    if (regular) {
-        const int sp = xcd + NUM_XCD * my_pi;
+    if (!L.split) {
+        if (merge_idx >= 0 || in_xcd >= L.pairs_per_xcd * L.n_row_tiles) return u;
+        const int sp = xcd + NUM_XCD * (in_xcd / L.n_row_tiles);
         if (sp >= L.n_pairs) return u;
         const int idx = L.n_row_tiles - 1 - in_xcd % L.n_row_tiles;      // position among the sub-pair's tiles
-        my_cnt = sub_pair_tiles(b.new_lens[sp / L.fan / b.num_kv_heads], G, L.fan, sp);
-        if (idx >= my_cnt) return u;                     // most workgroups of a ragged batch leave here
+        if (idx >= sub_pair_tiles(b.new_lens[sp / L.fan / b.num_kv_heads], G, L.fan, sp)) return u;
         u.pair = sp / L.fan;
         u.tile = sp % L.fan + L.fan * idx;
-        my_idx = idx;
-        if (!L.split) return u;
-    } else if (!L.split) {
         return u;
     }
     // lane pi (mod 32) looks at pair xcd + 8 pi
@@ -237,25 +237,20 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
     const int rem = total % CU_PER_XCD;
     const int parts = split_factor(rem, total / CU_PER_XCD, L.uneven);
-    if (parts == 1) return u;
-    u.rows_only = rows_only_of(rem, total / CU_PER_XCD);                            // regular: whole unit; extra: nothing to do (pair < 0)
-    u.min_tiles = total < CU_PER_XCD ? MIN_TILES_PER_PART_UNDERFILLED : MIN_TILES_PER_PART;
-    u.uneven = L.uneven ? uneven_of(rem) : 0;
     const int first_tail = total - rem;
-    if (regular) {
-        const int before_mine = __builtin_amdgcn_readfirstlane(wave_sum32(pi < my_pi ? cnt : 0));
-        const int ordinal = before_mine + my_cnt - 1 - my_idx;
-        if (ordinal >= first_tail) {
-            u.parts = parts;
-            u.slot = ordinal - first_tail;
-        }
-        return u;
+    int ordinal, slot = 0, part = 0;
+    if (merge_idx < 0 && in_xcd < total) {
+        ordinal = in_xcd;                                    // a whole unit, or piece 0 of a tail unit
+        slot = ordinal - first_tail;
+    } else {
+        if (parts == 1) return u;
+        const int e = in_xcd - total;
+        const int shares = (L.uneven && uneven_of(rem) > 0) ? 1 : parts;     // merge workgroups per unit
+        slot = merge_idx >= 0 ? merge_idx / shares : e / (parts - 1);
+        part = merge_idx >= 0 ? merge_idx % shares : 1 + e % (parts - 1);
+        if (slot >= rem) return u;
+        ordinal = first_tail + slot;
     }
-    const int e = in_xcd - n_regular;
-    const int shares = u.uneven > 0 ? 1 : parts;             // merge workgroups per unit
-    const int slot = merge_idx >= 0 ? merge_idx / shares : e / (parts - 1), part = merge_idx >= 0 ? merge_idx % shares : 1 + e % (parts - 1);
-    if (slot >= rem) return u;
-    const int ordinal = first_tail + slot;
     // the pair that holds this ordinal: the first one whose inclusive running count exceeds it
     int incl = cnt;
 #pragma unroll
@@ -270,9 +265,14 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int hit_sp = xcd + NUM_XCD * hit_pi;
     u.pair = hit_sp / L.fan;
     u.tile = hit_sp % L.fan + L.fan * (hit_incl - 1 - ordinal);   // position = cnt - 1 - (ordinal - exclusive count)
-    u.parts = parts;
-    u.part = part;
-    u.slot = slot;
+    if (parts > 1 && ordinal >= first_tail) {                // a tail unit
+        u.parts = parts;
+        u.part = part;
+        u.slot = slot;
+        u.rows_only = rows_only_of(rem, total / CU_PER_XCD);
+        u.min_tiles = total < CU_PER_XCD ? MIN_TILES_PER_PART_UNDERFILLED : MIN_TILES_PER_PART;
+        u.uneven = L.uneven ? uneven_of(rem) : 0;
+    }
     return u;
 }
 
@@ -951,7 +951,18 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
             any = any || split_factor((int)(units[x] % CU_PER_XCD), (int)(units[x] / CU_PER_XCD), L.uneven) > 1;
         if (!any) L.split = 0;
     }
-    const long long per_xcd = pairs_per_xcd * n_row_tiles + (L.split ? EXTRA_PER_XCD : 0);
+    long long slots = pairs_per_xcd * n_row_tiles;                       // one per row tile of the longest request, per pair
+    if (L.split && fan == 1) {
+        // With cutting, workgroup j of an XCD takes the XCD's unit j, so the grid only has to cover the units there
+        // are.  An XCD holds at most ceil(Hkv / 8) pairs of a request, and the row tiles of all requests number at
+        // most T G / 256 + B: a batch of one long request and many short ones gets a grid of about its real size
+        // instead of one with the longest request's row tiles for every pair (an empty workgroup still holds a
+        // compute unit for about a microsecond).
+        const long long bound = (long long)((b.num_kv_heads + NUM_XCD - 1) / NUM_XCD) *
+                                ((long long)b.total_new_tokens * G / BR + b.num_reqs);
+        slots = slots < bound ? slots : bound;
+    }
+    const long long per_xcd = slots + (L.split ? EXTRA_PER_XCD : 0);
     const long long grid = NUM_XCD * per_xcd;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)

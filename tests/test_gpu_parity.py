@@ -159,6 +159,10 @@ CUT_CASES = [
     ("uneven_short", "causal", 28, 4, [500, 520], [878, 878]),      # 25 units per XCD, too short to cut: whole units
     ("uneven_cross", "cross", 32, 8, [9000], [1088]),               # 17 units per XCD, no mask
     ("uneven_after_round", "causal", 56, 8, [5000], [2100]),        # 58 units per XCD = a full round + 26: k = 5
+    # one long request and many short ones: the grid is sized by the batch's row tiles, not by the longest request
+    ("long_and_short", "causal", 32, 8, [0] + [100] * 31, [2048] + [1] * 31),
+    ("long_and_short_h4", "causal", 28, 4, [300] + [50] * 20, [1500] + [3] * 20),
+    ("long_and_empty", "causal", 16, 16, [40, 0, 7, 5000], [0, 0, 0, 700]),     # 16 KV heads: two pairs of a request per XCD
     ("halve_ragged", "causal", 28, 4, [300, 1056, 0, 77], [100, 37, 150, 3]),   # last row tiles of 188, 3, 26, 21 rows
 ]
 
