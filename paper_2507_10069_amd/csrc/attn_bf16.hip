@@ -105,7 +105,7 @@ constexpr int PIECES_PER_XCD = 2 * CU_PER_XCD;           // tail units x pieces 
 constexpr int EXTRA_PER_XCD = CU_PER_XCD - 1;            // workgroups for pieces 1, 2, ... of an XCD's tail units
 constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
 constexpr int MIN_TILES_PER_PART_UNDERFILLED = 8;        // ... unless the compute units would stay idle otherwise
-constexpr int SPLIT_MAX_PAIRS_PER_XCD = 32;              // planning scans an XCD's pairs: keep that short
+constexpr int SPLIT_MAX_PAIRS_PER_XCD = 64;              // planning scans an XCD's pairs, one per lane of a wave
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
 
 // With fewer than 8 (request, KV head) pairs some XCDs would get no work, so each pair is dealt to `fan`
@@ -196,18 +196,18 @@ __device__ inline bool uneven_cuttable(int n_tiles, int k, int limit_min)
     return n_tiles - split >= MIN_TILES_PER_PART && (split + 1) * BC - 1 <= limit_min;
 }
 
-__device__ inline int wave_sum32(int x)                  // sum over lanes 0..31 (and, separately, 32..63)
+__device__ inline int wave_sum64(int x)                  // sum over the wave's 64 lanes, in every lane
 {
 #pragma unroll
-    for (int d = 1; d < 32; d <<= 1) x += __shfl_xor(x, d, 64);
+    for (int d = 1; d < 64; d <<= 1) x += __shfl_xor(x, d, 64);
     return x;
 }
 
 // Plan of workgroup `in_xcd` of XCD `xcd`.
-// Without cutting (L.split == 0: no workspace, or more than 32 pairs on an XCD) the grid has as many slots per
+// Without cutting (L.split == 0: no workspace, or more than 64 pairs on an XCD) the grid has as many slots per
 // pair as the longest request needs (pair-major, row tiles descending) and a workgroup whose slot holds no
 // row tile leaves at once.
-// With cutting, the lanes of each wave scan the XCD's pairs (at most 32), which gives every workgroup the number
+// With cutting, the lanes of each wave scan the XCD's pairs (at most 64), which gives every workgroup the number
 // of units of its XCD and of every pair before it.  Workgroup j then takes unit j in the same order (pair-major,
 // row tiles descending); the workgroups after the last unit do pieces 1, 2, ... of the tail units; what is left
 // of the grid (sized for the longest request) has nothing to do.  All empty workgroups thus lie at the end of
@@ -229,12 +229,12 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
         u.tile = sp % L.fan + L.fan * idx;
         return u;
     }
-    // lane pi (mod 32) looks at pair xcd + 8 pi
-    const int pi = threadIdx.x & 31;
+    // lane pi looks at pair xcd + 8 pi
+    const int pi = threadIdx.x & 63;
     const int lane_sp = xcd + NUM_XCD * pi;
     const int cnt = (pi < L.pairs_per_xcd && lane_sp < L.n_pairs)
                         ? sub_pair_tiles(b.new_lens[lane_sp / L.fan / b.num_kv_heads], G, L.fan, lane_sp) : 0;
-    const int total = __builtin_amdgcn_readfirstlane(wave_sum32(cnt));
+    const int total = __builtin_amdgcn_readfirstlane(wave_sum64(cnt));
     const int rem = total % CU_PER_XCD;
     const int parts = split_factor(rem, total / CU_PER_XCD, L.uneven);
     const int first_tail = total - rem;
@@ -254,11 +254,11 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     // the pair that holds this ordinal: the first one whose inclusive running count exceeds it
     int incl = cnt;
 #pragma unroll
-    for (int d = 1; d < 32; d <<= 1) {
-        const int up = __shfl_up(incl, d, 32);
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
         if (pi >= d) incl += up;
     }
-    const unsigned long long hit = __builtin_amdgcn_ballot_w64(incl > ordinal) & 0xffffffffull;
+    const unsigned long long hit = __builtin_amdgcn_ballot_w64(incl > ordinal);
     if (hit == 0) return u;
     const int hit_pi = __builtin_ctzll(hit);
     const int hit_incl = __builtin_amdgcn_readlane(incl, hit_pi);

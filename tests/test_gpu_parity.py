@@ -162,6 +162,10 @@ CUT_CASES = [
     # one long request and many short ones: the grid is sized by the batch's row tiles, not by the longest request
     ("long_and_short", "causal", 32, 8, [0] + [100] * 31, [2048] + [1] * 31),
     ("long_and_short_h4", "causal", 28, 4, [300] + [50] * 20, [1500] + [3] * 20),
+    ("many_pairs", "causal", 28, 4, [int(x) for x in np.random.default_rng(5).integers(0, 2500, 100)],
+     [int(x) for x in np.random.default_rng(6).integers(0, 400, 100)]),          # 400 pairs: 50 per XCD, one per lane of the scan
+    ("too_many_pairs", "causal", 32, 8, [int(x) for x in np.random.default_rng(7).integers(0, 900, 70)],
+     [int(x) for x in np.random.default_rng(8).integers(1, 300, 70)]),           # 560 pairs: 70 per XCD, no scan, no cuts
     ("long_and_empty", "causal", 16, 16, [40, 0, 7, 5000], [0, 0, 0, 700]),     # 16 KV heads: two pairs of a request per XCD
     ("halve_ragged", "causal", 28, 4, [300, 1056, 0, 77], [100, 37, 150, 3]),   # last row tiles of 188, 3, 26, 21 rows
 ]
