@@ -56,6 +56,7 @@ using namespace bf16attn;
 
 constexpr int BR = 256;           // rows per workgroup
 constexpr int PF_DIST = 2;          // MFMA operands are read from LDS this many slices ahead of their use
+constexpr int OUT_STRIDE = 272;     // bytes between output rows staged in LDS: 256 + 16, which spreads the banks
 
 // Identity the optimiser cannot see through.  Inside the main loop, addresses derived from a per-lane
 // base by one XOR or add are recomputed from such a copy every iteration; hoisted out of the loop as
@@ -303,6 +304,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int kvh = pair % b.num_kv_heads;
     const int r = pair / b.num_kv_heads;
 
+    // The page ids of the unit's first 64 key tiles are asked for right away, before the request's lengths are
+    // known (the load needs only the request): one memory latency less between launch and first MFMA.  Lane k
+    // will fetch 16-key block 4 k + wave / 2 of tile k; what entries past the context hold is never used.
+    const int32_t* __restrict__ pt = b.page_table + (long long)r * b.max_pages;
+    const int blk_early = (threadIdx.x & 63) * 4 + (threadIdx.x >> 7);
+    const int pg_early = pt[min(blk_early >> b.page_shift, b.max_pages - 1)];
+
     const int N = b.new_lens[r];
     const int n_rows = N * G;                                // rows of this (request, KV head)
     const int row0 = tile * BR;
@@ -362,7 +370,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 #pragma unroll
     for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(qp + 16 * s);
 
-    const int32_t* __restrict__ pt = b.page_table + (long long)r * b.max_pages;
     // ---- global -> LDS.  Tiles go straight from global memory into LDS (global_load_lds_dwordx4: lane i
     //      of a wave writes 16 bytes at base + 16 i), 4 rows of 256 bytes per instruction.  Wave w brings
     //      rows 8w .. 8w+7 of the K tile and of the V tile (two instructions each), all from logical
@@ -534,7 +541,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     if (n_tiles > 0) {
         // ---- prologue: the first tiles K(0), V(0), K(1), V(1), K(2) of this workgroup's range on their way
         //      to LDS (tile numbers in the comments below are relative to t_begin; ring slots follow them)
-        refill_pages(t_begin);
+        const int last_lane = (n_blocks_valid - 1 - (wave >> 1)) >> 2;      // last lane whose block of tile `lane` holds tokens
+        if (t_begin == 0 && last_lane >= 0) {
+            // the ids asked for at the start; lanes past the context take the wave's last block that holds tokens
+            // (any block inside the context will do there: its keys are masked and its V rows zeroed)
+            const int src_lane = min(last_lane, 63);
+            const int id = min(max(pg_early, 0), b.num_pages - 1);
+            const int page = lane <= src_lane ? id : __builtin_amdgcn_readlane(id, src_lane);
+            const int blk = min(blk_early, src_lane * 4 + (wave >> 1));
+            pg_vec = ((page * b.num_kv_heads + kvh) << b.page_shift) + (blk & ((1 << b.page_shift) - 1));
+            pg_base = 0;
+        } else {
+            refill_pages(t_begin);
+        }
         load_k(t_begin, 0);
         load_v(t_begin, 0);
         load_k(t_begin + 1, 1);
@@ -555,8 +574,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 if (i + 1 >= n_clear) zero_v_tail(i + 1, (R + 1) & 3);
                 __syncthreads();
             }
-            return;
-        }
+        } else {
 
         f32x16 sc[2][2];                                     // scores of tile i live in sc[i & 1]
 
@@ -756,6 +774,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             case 2: exp_tile(sc[0], pf); pv_tile(2, pf); break;
             default: exp_tile(sc[1], pf); pv_tile(3, pf); break;
         }
+        }                                                    // active
     }
 
     // ---- epilogue.  The row bookkeeping is recomputed from an opaque copy of the thread index so that
@@ -766,6 +785,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         if (cut > 1) {
             // a piece of a cut unit: unnormalised accumulator, running maximum and row sum go to the
             // workspace, one coalesced row of 512 floats per register; attn_bf16_merge_kernel finishes
+            if (!active) return;                             // a wave without rows has nothing to hand over
             float* __restrict__ ws = part_base(a.workspace, xcd, plan.slot, plan.parts, plan.part) + t2;
             const float l_part = pair_sum(l_run);
 #pragma unroll
@@ -776,15 +796,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             ws[65 * NTHREADS] = l_part;
             return;
         }
-        const int e_l32 = t2 & 31, e_h32 = (t2 >> 5) & 1;
-        const int e_row = row0 + (t2 >> 6) * 32 + e_l32;
-        if (e_row >= n_rows) return;
-        const int e_tok = e_row / G;
-        const int e_hq = kvh * G + (e_row - e_tok * G);
-        const long long e_qrow = (long long)b.cu_new_lens[r] + e_tok;
+        // The normalised rows go to global memory through LDS, so that a store instruction writes four whole
+        // rows of 256 bytes (16 lanes x 16 bytes each): written straight from the accumulator layout, every
+        // lane of an instruction would touch a different row, which costs about 2 us per workgroup.  The rings
+        // are free once every wave's fetches have landed and every wave is past its last read.
+        __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0)
+        __syncthreads();
+        if (!active) return;
+        const int e_wave = t2 >> 6, e_lane = t2 & 63;
+        const int e_l32 = e_lane & 31, e_h32 = e_lane >> 5;
         const float l_tot = pair_sum(l_run);                 // partner lane is in the same state
         const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;
-        __bf16* __restrict__ op = (__bf16*)a.out + (e_qrow * b.num_q_heads + e_hq) * D;
+        unsigned char* stage = smem + e_wave * (32 * OUT_STRIDE);        // this wave's 32 rows, OUT_STRIDE bytes apart
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
@@ -793,11 +816,28 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 bf16x4 w;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[nb][4 * v4 + e] * inv);
-                *(bf16x4*)(op + 32 * nb + 8 * v4 + 4 * e_h32) = w;
+                *(bf16x4*)(stage + e_l32 * OUT_STRIDE + 2 * (32 * nb + 8 * v4 + 4 * e_h32)) = w;
             }
-        if (a.lse != nullptr && e_h32 == 0)
-            a.lse[e_qrow * b.num_q_heads + e_hq] =
+        const int e_row = row0 + e_wave * 32 + e_l32;
+        if (a.lse != nullptr && e_h32 == 0 && e_row < n_rows) {
+            const int e_tok = e_row / G;
+            a.lse[((long long)b.cu_new_lens[r] + e_tok) * b.num_q_heads + kvh * G + (e_row - e_tok * G)] =
                 (l_tot > 0.f) ? m_run * b.softmax_scale + logf(l_tot) : -INFINITY;
+        }
+        // the wave's own LDS writes are visible to its own reads once they have completed
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const long long q_row0 = (long long)b.cu_new_lens[r];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int in_wave = (e_lane >> 4) + 4 * j;       // lanes 16k .. 16k+15 take row 4j + k
+            const int row = row0 + e_wave * 32 + in_wave;
+            if (row < n_rows) {
+                const int tok = row / G;
+                const int hq = kvh * G + (row - tok * G);
+                const uint4 v = *(const uint4*)(stage + in_wave * OUT_STRIDE + (e_lane & 15) * 16);
+                *(uint4*)((__bf16*)a.out + ((q_row0 + tok) * b.num_q_heads + hq) * D + (e_lane & 15) * 8) = v;
+            }
+        }
     }
 }
 
