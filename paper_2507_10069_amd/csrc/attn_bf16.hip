@@ -358,12 +358,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int my_row = wrow0 + l32;
     const int row_c = min(my_row, n_rows - 1);
     const int tok = row_c / G;                               // new-token index of this lane's row
-    const int hq = kvh * G + (row_c - tok * G);              // its query head
     const int limit = CAUSAL ? P + tok : P - 1;              // last visible key of this lane's row
     const int wave_min_limit = CAUSAL ? P + min(wrow0, n_rows - 1) / G : P - 1;
     // tiles 0 .. n_clear-1 lie entirely below every row's limit in this wave: no mask needed
     const int n_clear = (wave_min_limit + 1) / BC;
 
+    const int hq = kvh * G + (row_c - tok * G);              // its query head
     const long long q_row = (long long)b.cu_new_lens[r] + tok;
     const __bf16* __restrict__ qp = (const __bf16*)a.q + (q_row * b.num_q_heads + hq) * D + 8 * h32;
     bf16x8 qf[8];
@@ -827,16 +827,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         // the wave's own LDS writes are visible to its own reads once they have completed
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         const long long q_row0 = (long long)b.cu_new_lens[r];
+        const int t_add = 4 / G, g_add = 4 - t_add * G;      // row + 4 is token + t_add, head + g_add (mod G)
+        const int first = row0 + e_wave * 32 + (e_lane >> 4);
+        int o_tok = first / G, o_g = first - o_tok * G;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int in_wave = (e_lane >> 4) + 4 * j;       // lanes 16k .. 16k+15 take row 4j + k
-            const int row = row0 + e_wave * 32 + in_wave;
-            if (row < n_rows) {
-                const int tok = row / G;
-                const int hq = kvh * G + (row - tok * G);
+            if (first + 4 * j < n_rows) {
                 const uint4 v = *(const uint4*)(stage + in_wave * OUT_STRIDE + (e_lane & 15) * 16);
-                *(uint4*)((__bf16*)a.out + ((q_row0 + tok) * b.num_q_heads + hq) * D + (e_lane & 15) * 8) = v;
+                *(uint4*)((__bf16*)a.out + ((q_row0 + o_tok) * b.num_q_heads + kvh * G + o_g) * D + (e_lane & 15) * 8) = v;
             }
+            o_tok += t_add;
+            o_g += g_add;
+            if (o_g >= G) { o_g -= G; o_tok += 1; }
         }
     }
 }
