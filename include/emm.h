@@ -22,7 +22,9 @@
  *   - Every pointer marked "device" is memory of the current HIP device, owned by the caller; the
  *     library allocates and frees nothing and keeps no state between calls.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
- *     return without waiting for it.  Errors are reported by return code only.
+ *     return without waiting for it.  Errors are reported by return code only.  Everything a call was
+ *     given in device memory, the batch's four arrays included, must stay allocated and unchanged until
+ *     that work has finished.
  *   - Host-side checks cover the scalar fields, null pointers and 16-byte alignment of tensor
  *     pointers.  Device-resident arrays (page table, lengths) are trusted; check host copies of
  *     them with emm_validate_batch_host.

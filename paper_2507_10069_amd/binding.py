@@ -113,11 +113,17 @@ def _stream(stream) -> Optional[int]:
 def make_batch(*, num_reqs, num_q_heads, num_kv_heads, head_dim, page_size, num_pages, max_pages_per_req,
                total_new_tokens, max_new_len, dtype, softmax_scale, page_table=None, prefix_lens=None,
                new_lens=None, cu_new_lens=None) -> emm_batch:
-    """Fill the descriptor; the four arrays are int32 device tensors (or None for host-only calls)."""
+    """Fill the descriptor; the four arrays are int32 device tensors (or None for host-only calls).
+
+    The descriptor holds raw device addresses, so the returned object also keeps the four tensors alive: a
+    tensor created in the call's argument list would otherwise be freed, and its memory handed to the next
+    allocation, before the kernels that read it have run."""
     code = {"f32": EMM_F32, "bf16": EMM_BF16}.get(dtype, dtype)
-    return emm_batch(num_reqs, num_q_heads, num_kv_heads, head_dim, page_size, num_pages, max_pages_per_req,
-                     total_new_tokens, max_new_len, code, float(softmax_scale), 0,
-                     _ptr(page_table), _ptr(prefix_lens), _ptr(new_lens), _ptr(cu_new_lens))
+    batch = emm_batch(num_reqs, num_q_heads, num_kv_heads, head_dim, page_size, num_pages, max_pages_per_req,
+                      total_new_tokens, max_new_len, code, float(softmax_scale), 0,
+                      _ptr(page_table), _ptr(prefix_lens), _ptr(new_lens), _ptr(cu_new_lens))
+    batch._keepalive = (page_table, prefix_lens, new_lens, cu_new_lens)
+    return batch
 
 
 def _check(status: int, where: str) -> None:

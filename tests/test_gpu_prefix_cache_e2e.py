@@ -161,3 +161,59 @@ def test_cached_prefixes_give_the_answers_of_full_prefill():
     assert st["evictions"] > 0                       # pages were reused for other content along the way
     assert st["live_requests"] == 0 and st["free_pages"] + st["cached_pages"] == NUM_PAGES
     PC.emm_prefix_cache_destroy(cache)
+
+
+def test_chunked_prefill_equals_one_shot():
+    """Section 2.2 (chunked prefill): a long prompt prefilled in segments, each segment attending to the K/V that
+    the earlier segments left in the pool, gives the rows of one prefill over the whole prompt.  The segment
+    boundaries are not page aligned, and two requests of different lengths run in the same batches."""
+    import torch
+    rng = np.random.default_rng(99)
+    rows = _Rows(11)
+    pools = tuple(torch.full((NUM_PAGES * 4, HKV, PS, D), 1e30, dtype=torch.bfloat16, device="cuda:0") for _ in range(2))
+    prompts = [rng.integers(0, 30000, 500).tolist(), rng.integers(0, 30000, 333).tolist()]
+    perm = rng.permutation(NUM_PAGES * 4)
+    tables = []
+    used = 0
+    for p in prompts:
+        n_pages = -(-len(p) // PS)
+        row = np.full(MAX_PAGES * 2, -1, dtype=np.int32)
+        row[:n_pages] = perm[used:used + n_pages]
+        used += n_pages
+        tables.append(row)
+    bounds = [[0, 300, 417, 500], [0, 150, 151, 333]]        # three segments each; the second one's middle segment is one token
+    got = [[], []]
+    for seg in range(3):
+        reqs = [(prompts[i][:bounds[i][seg + 1]], tables[i], bounds[i][seg]) for i in range(2)]
+        outs = _run_batch_wide(torch, pools, rows, reqs)
+        for i in range(2):
+            got[i].append(outs[i])
+    for i in range(2):
+        _check(np.concatenate(got[i]), _expect(rows, prompts[i], 0), ("chunked", i))
+
+
+def _run_batch_wide(torch, pools, rows, reqs):
+    """As _run_batch, for page-table rows of 2 * MAX_PAGES entries over a pool of 4 * NUM_PAGES pages."""
+    k_pool, v_pool = pools
+    new_lens = np.array([len(t) - pl for t, _, pl in reqs], dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(new_lens)]).astype(np.int32)
+    q = np.concatenate([rows.rows("q", t[pl:], pl) for t, _, pl in reqs])
+    k_new = np.concatenate([rows.rows("k", t[pl:], pl) for t, _, pl in reqs])
+    v_new = np.concatenate([rows.rows("v", t[pl:], pl) for t, _, pl in reqs])
+    pt = torch.from_numpy(np.stack([r for _, r, _ in reqs]).astype(np.int32)).to("cuda:0")
+    pl_d = torch.tensor([pl for _, _, pl in reqs], dtype=torch.int32, device="cuda:0")
+    nl_d = torch.from_numpy(new_lens).to("cuda:0")          # held until the kernels have run: the batch stores addresses
+    cu_d = torch.from_numpy(cu).to("cuda:0")
+    batch = B.make_batch(num_reqs=len(reqs), num_q_heads=H, num_kv_heads=HKV, head_dim=D, page_size=PS,
+                         num_pages=NUM_PAGES * 4, max_pages_per_req=MAX_PAGES * 2, total_new_tokens=int(cu[-1]),
+                         max_new_len=int(new_lens.max()), dtype="bf16", softmax_scale=SCALE, page_table=pt,
+                         prefix_lens=pl_d, new_lens=nl_d, cu_new_lens=cu_d)
+    assert B.emm_validate_batch_host(batch, pt.cpu().numpy(), pl_d.cpu().numpy(), new_lens, cu, True) == B.EMM_OK
+    q_d, k_d, v_d = _dev_bf16(q, torch), _dev_bf16(k_new, torch), _dev_bf16(v_new, torch)
+    out = torch.empty_like(q_d)
+    ws = torch.empty(max(B.emm_prefill_attn_workspace_size(batch), 16), dtype=torch.uint8, device="cuda:0")
+    B.emm_kv_scatter(batch, k_d, v_d, k_pool, v_pool)
+    B.emm_prefill_attn(batch, q_d, k_pool, v_pool, out, None, ws)
+    torch.cuda.synchronize()
+    o = out.to(torch.float32).cpu().numpy().astype(np.float64)
+    return [o[cu[i]:cu[i + 1]] for i in range(len(reqs))]
