@@ -179,9 +179,12 @@ def emm_decode_attn_shared_workspace_size(batch: emm_batch, shared: emm_shared_p
 def make_shared_prefix(num_units: int, unit_first_req=None, unit_num_reqs=None, unit_shared_len=None, req_unit=None,
                        req_shared_len=None, planned_tiles: int = 0, max_own_tiles: int = 0,
                        max_unit_tiles: int = 0) -> emm_shared_prefix:
-    """Fill the descriptor; the five arrays are int32 device tensors."""
-    return emm_shared_prefix(num_units, planned_tiles, max_own_tiles, max_unit_tiles, _ptr(unit_first_req), _ptr(unit_num_reqs), _ptr(unit_shared_len),
-                             _ptr(req_unit), _ptr(req_shared_len))
+    """Fill the descriptor; the five arrays are int32 device tensors, which the returned object keeps alive (it
+    holds their addresses only)."""
+    shared = emm_shared_prefix(num_units, planned_tiles, max_own_tiles, max_unit_tiles, _ptr(unit_first_req),
+                               _ptr(unit_num_reqs), _ptr(unit_shared_len), _ptr(req_unit), _ptr(req_shared_len))
+    shared._keepalive = (unit_first_req, unit_num_reqs, unit_shared_len, req_unit, req_shared_len)
+    return shared
 
 
 def emm_decode_attn_shared(batch: emm_batch, shared: emm_shared_prefix, q, k_cache, v_cache, out, lse=None,

@@ -258,3 +258,24 @@ def test_decode_step_argument_checks():
     assert step(batch=_batch(num_reqs=4, total_new_tokens=4, max_new_len=1, num_q_heads=34, num_kv_heads=2)) == B.EMM_ERR_UNSUPPORTED
     assert step(batch=_batch(num_reqs=4, total_new_tokens=4, max_new_len=1, dtype="f32", head_dim=64)) == B.EMM_ERR_UNSUPPORTED
     assert step(batch=_batch(num_reqs=0, total_new_tokens=0, max_new_len=0)) == B.EMM_OK
+
+
+def test_descriptors_keep_their_tensors_alive():
+    """The descriptors hold raw addresses; a tensor built in the argument list must not be freed under them."""
+    import gc
+    import weakref
+
+    class _Array:                                   # stands in for a device tensor
+        def data_ptr(self):
+            return 0x1000
+
+    a = _Array()
+    ref = weakref.ref(a)
+    batch = _batch(page_table=a)
+    shared = B.make_shared_prefix(0, unit_first_req=a)
+    del a
+    gc.collect()
+    assert ref() is not None and batch._keepalive[0] is ref() and shared._keepalive[0] is ref()
+    del batch, shared
+    gc.collect()
+    assert ref() is None
