@@ -26,8 +26,11 @@
  *     given in device memory, the batch's four arrays included, must stay allocated and unchanged until
  *     that work has finished.
  *   - Host-side checks cover the scalar fields, null pointers and 16-byte alignment of tensor
- *     pointers.  Device-resident arrays (page table, lengths) are trusted; check host copies of
- *     them with emm_validate_batch_host.
+ *     pointers.  Device-resident arrays (page table, lengths, shared-prefix units) cannot be checked
+ *     there: check host copies of them with emm_validate_batch_host.  The kernels force whatever
+ *     those arrays hold into the range the scalar fields allow (page ids into the pool, lengths into
+ *     the page-table row and the packed tensors), so inconsistent arrays give meaningless results but
+ *     no access outside the buffers that were passed.
  *   - Pool layout: [num_pages][num_kv_heads][page_size][head_dim], K and V in separate pools.
  *     Logical token slot i of request r lives in page page_table[r][i / page_size] at offset
  *     i % page_size.  Packed layouts: q, out [T][num_q_heads][head_dim]; k_new, v_new

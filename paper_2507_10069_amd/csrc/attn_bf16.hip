@@ -225,7 +225,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
         const int sp = xcd + NUM_XCD * (in_xcd / L.n_row_tiles);
         if (sp >= L.n_pairs) return u;
         const int idx = L.n_row_tiles - 1 - in_xcd % L.n_row_tiles;      // position among the sub-pair's tiles
-        if (idx >= sub_pair_tiles(b.new_lens[sp / L.fan / b.num_kv_heads], G, L.fan, sp)) return u;
+        if (idx >= sub_pair_tiles(safe_new_len(b, sp / L.fan / b.num_kv_heads, false), G, L.fan, sp)) return u;
         u.pair = sp / L.fan;
         u.tile = sp % L.fan + L.fan * idx;
         return u;
@@ -234,7 +234,7 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     const int pi = threadIdx.x & 63;
     const int lane_sp = xcd + NUM_XCD * pi;
     const int cnt = (pi < L.pairs_per_xcd && lane_sp < L.n_pairs)
-                        ? sub_pair_tiles(b.new_lens[lane_sp / L.fan / b.num_kv_heads], G, L.fan, lane_sp) : 0;
+                        ? sub_pair_tiles(safe_new_len(b, lane_sp / L.fan / b.num_kv_heads, false), G, L.fan, lane_sp) : 0;
     const int total = __builtin_amdgcn_readfirstlane(wave_sum64(cnt));
     const int rem = total % CU_PER_XCD;
     const int parts = split_factor(rem, total / CU_PER_XCD, L.uneven);
@@ -311,11 +311,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int blk_early = (threadIdx.x & 63) * 4 + (threadIdx.x >> 7);
     const int pg_early = pt[min(blk_early >> b.page_shift, b.max_pages - 1)];
 
-    const int N = b.new_lens[r];
+    // (lengths forced into what the page table and the packed tensors can hold: see safe_new_len)
+    const int N = safe_new_len(b, r, CAUSAL);
     const int n_rows = N * G;                                // rows of this (request, KV head)
     const int row0 = tile * BR;
     if (row0 >= n_rows) return;                              // uniform over the workgroup
-    const int P = b.prefix_lens[r];
+    const int P = safe_prefix_len(b, r, CAUSAL ? N : 0);
+    const int first_row = safe_first_row(b, r, N);           // of the request in the packed tensors
     const int ctx_len = CAUSAL ? P + N : P;                  // slots of this request that hold tokens
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = CAUSAL ? P + last_row / G + 1 : P;    // keys this row tile can see
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     const int n_clear = (wave_min_limit + 1) / BC;
 
     const int hq = kvh * G + (row_c - tok * G);              // its query head
-    const long long q_row = (long long)b.cu_new_lens[r] + tok;
+    const long long q_row = (long long)first_row + tok;
     const __bf16* __restrict__ qp = (const __bf16*)a.q + (q_row * b.num_q_heads + hq) * D + 8 * h32;
     bf16x8 qf[8];
 #pragma unroll
@@ -821,12 +823,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         const int e_row = row0 + e_wave * 32 + e_l32;
         if (a.lse != nullptr && e_h32 == 0 && e_row < n_rows) {
             const int e_tok = e_row / G;
-            a.lse[((long long)b.cu_new_lens[r] + e_tok) * b.num_q_heads + kvh * G + (e_row - e_tok * G)] =
+            a.lse[((long long)first_row + e_tok) * b.num_q_heads + kvh * G + (e_row - e_tok * G)] =
                 (l_tot > 0.f) ? m_run * b.softmax_scale + logf(l_tot) : -INFINITY;
         }
         // the wave's own LDS writes are visible to its own reads once they have completed
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        const long long q_row0 = (long long)b.cu_new_lens[r];
+        const long long q_row0 = first_row;
         const int t_add = 4 / G, g_add = 4 - t_add * G;      // row + 4 is token + t_add, head + g_add (mod G)
         const int first = row0 + e_wave * 32 + (e_lane >> 4);
         int o_tok = first / G, o_g = first - o_tok * G;
@@ -912,10 +914,11 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     if (plan.pair < 0) return;
     const int kvh = plan.pair % b.num_kv_heads;
     const int r = plan.pair / b.num_kv_heads;
-    const int N = b.new_lens[r];
+    const int N = safe_new_len(b, r, a.causal != 0);         // the same values as in the main kernel
     const int n_rows = N * G;
     const int row0 = plan.tile * BR;
-    const int P = b.prefix_lens[r];
+    if (row0 >= n_rows) return;
+    const int P = safe_prefix_len(b, r, a.causal ? N : 0);
     const int last_row = min(row0 + BR - 1, n_rows - 1);
     const int kv_len = a.causal ? P + last_row / G + 1 : P;
     const int limit_first_row = a.causal ? P + row0 / G : P - 1;
@@ -930,7 +933,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     if (row >= n_rows) return;
     const int tok = row / G;
     const int hq = kvh * G + (row - tok * G);
-    const long long q_row = (long long)b.cu_new_lens[r] + tok;
+    const long long q_row = (long long)safe_first_row(b, r, N) + tok;
     const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, plan.parts, 0);
     __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
     float* lse = (a.lse != nullptr && h32 == 0 && plan.part == 0) ? a.lse + q_row * b.num_q_heads + hq : nullptr;

@@ -97,11 +97,12 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int pair = blk % n_items, piece = blk / n_items;                // unit mode: pair = (unit, KV head)
     const int kvh = pair % b.num_kv_heads;
     const int unit = pair / b.num_kv_heads;                               // own part: this is the request itself
-    const int r = unit_mode ? sv.unit_first_req[unit] : unit;             // the request whose page table is read
+    // (what the device arrays hold is forced into range wherever an address depends on it: see safe_new_len)
+    const int r = unit_mode ? min(max(sv.unit_first_req[unit], 0), b.num_reqs - 1) : unit;   // the request whose page table is read
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    const int t_off = (SHARED && !unit_mode) ? sv.req_shared_len[r] / BK : 0;   // tiles a unit computes for this request
+    const int t_off = (SHARED && !unit_mode) ? max(sv.req_shared_len[r], 0) / BK : 0;   // tiles a unit computes for this request
     const int t_begin = t_off + piece * S.tiles_per_piece;
     // lane k of a wave holds where in the pool the 16-key block lies that this wave fetches for tile t_begin + k
     // (a piece has at most 60 tiles and fetches run two tiles ahead, so 64 lanes cover it).  Asked for before the lengths are
@@ -114,16 +115,17 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     bool direct;                                             // one piece and no unit: this workgroup writes the output
     if (!unit_mode) {
         if (b.new_lens[r] <= 0) return;                      // no query token
-        const int P = b.prefix_lens[r];
+        const int P = safe_prefix_len(b, r, CAUSAL ? 1 : 0);
         kv_len = CAUSAL ? P + 1 : P;                         // keys the query sees = slots that hold tokens
         const bool in_unit = SHARED && sv.req_unit[r] >= 0;
         n_pieces = own_pieces_of(kv_len, t_off, S.tiles_per_piece, in_unit);
         n_rows = G;
         direct = n_pieces == 1 && !in_unit;
     } else {
-        kv_len = sv.unit_shared_len[unit];                   // a multiple of the tile: no mask, no ragged tail
+        // a multiple of the tile: no mask, no ragged tail
+        kv_len = (int)min((long long)max(sv.unit_shared_len[unit], 0), (long long)b.max_pages * b.page_size) / BK * BK;
         n_pieces = (kv_len / BK + S.tiles_per_piece - 1) / S.tiles_per_piece;
-        n_rows = min(sv.unit_num_reqs[unit] * G, MAX_ROWS);
+        n_rows = min(max(sv.unit_num_reqs[unit], 1) * G, MAX_ROWS);
         direct = false;
     }
     if (piece >= n_pieces) return;
@@ -139,9 +141,9 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     // every wave holds the same query rows: the G heads of the request, or in unit mode the G heads of each
     // of the unit's requests; the remaining columns of the MFMA repeat the last row and are discarded
     const int my_row = min(l32, n_rows - 1);
-    const int my_req = unit_mode ? r + my_row / G : r;
+    const int my_req = unit_mode ? min(r + my_row / G, b.num_reqs - 1) : r;
     const int hq = kvh * G + (unit_mode ? my_row % G : my_row);
-    const long long q_row = min((long long)b.cu_new_lens[my_req], (long long)b.total_new_tokens - 1);
+    const long long q_row = safe_first_row(b, my_req, 1);
     const __bf16* __restrict__ qp = (const __bf16*)a.q + (q_row * b.num_q_heads + hq) * D + 8 * h32;
     bf16x8 qf[8];
 #pragma unroll
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     // FUSED: the tile of this piece that holds the query token's own slot (none in most workgroups); its K/V
     // row comes from k_new / v_new, written by the waves that fetched the rows it replaces
     const int new_tile = (FUSED && !unit_mode) ? (kv_len - 1) / BK - t_begin : -1;
-    const long long new_row_bytes = ((long long)b.cu_new_lens[r] * b.num_kv_heads + kvh) * (D * 2);
+    const long long new_row_bytes = ((long long)safe_first_row(b, r, 1) * b.num_kv_heads + kvh) * (D * 2);
     auto patch_new_row = [&](int i, int slot) {
         if (FUSED && i == new_tile) {
             const int kk = (kv_len - 1) % BK;                                  // key within the tile
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
             }
             if (direct) {
                 const int head = kvh * G + row;
-                const long long q_own = b.cu_new_lens[r];
+                const long long q_own = safe_first_row(b, r, 1);
                 ((__bf16*)a.out)[(q_own * b.num_q_heads + head) * D + ch] = (__bf16)(l_tot > 0.f ? acc / l_tot : 0.f);
                 if (ch == 0 && a.lse != nullptr)
                     a.lse[q_own * b.num_q_heads + head] = (l_tot > 0.f) ? m_all * b.softmax_scale + logf(l_tot) : -INFINITY;
@@ -376,17 +378,21 @@ __global__ __launch_bounds__(MERGE_GROUPS * D) void attn_bf16_decode_merge_kerne
     const int kvh = pair % b.num_kv_heads;
     const int r = pair / b.num_kv_heads;
     if (b.new_lens[r] <= 0) return;
-    const int P = b.prefix_lens[r];
+    const int P = safe_prefix_len(b, r, CAUSAL ? 1 : 0);
     // the records of this row: n_own from the request's own workgroups, then n_unit from its unit's
-    const int unit = SHARED ? sv.req_unit[r] : -1;
-    const int n_own = own_pieces_of(CAUSAL ? P + 1 : P, SHARED ? sv.req_shared_len[r] / BK : 0, S.tiles_per_piece, unit >= 0);
+    // (counts and positions forced into what the workspace holds, whatever the device arrays say)
+    const int unit = SHARED ? min(max(sv.req_unit[r], -1), sv.num_units - 1) : -1;
+    const int n_own = min(own_pieces_of(CAUSAL ? P + 1 : P, SHARED ? max(sv.req_shared_len[r], 0) / BK : 0, S.tiles_per_piece, unit >= 0),
+                          S.pieces_max);
     if (unit < 0 && n_own == 1) return;
     int n_unit = 0;
     const float* __restrict__ rec_unit = nullptr;
     if (unit >= 0) {
-        n_unit = (sv.unit_shared_len[unit] / BK + S.tiles_per_piece - 1) / S.tiles_per_piece;
+        const int shared_len = (int)min((long long)max(sv.unit_shared_len[unit], 0), (long long)b.max_pages * b.page_size) / BK * BK;
+        n_unit = min((shared_len / BK + S.tiles_per_piece - 1) / S.tiles_per_piece, S.pieces_unit);
+        const int member = min(max(r - sv.unit_first_req[unit], 0), MAX_ROWS / G - 1);       // position of the request in its unit
         rec_unit = (const float*)a.workspace + unit_records_offset(S) +
-                   ((size_t)(unit * b.num_kv_heads + kvh) * S.pieces_unit * MAX_ROWS + (r - sv.unit_first_req[unit]) * G + row) * REC_FLOATS;
+                   ((size_t)(unit * b.num_kv_heads + kvh) * S.pieces_unit * MAX_ROWS + member * G + row) * REC_FLOATS;
     }
     const int n_pieces = n_own + n_unit;
     const float c_log2 = b.softmax_scale * 1.44269504088896340736f;
@@ -445,7 +451,7 @@ __global__ __launch_bounds__(MERGE_GROUPS * D) void attn_bf16_decode_merge_kerne
         for (int g = 0; g < MERGE_GROUPS; ++g) acc += acc_s[g][ch];
 #pragma unroll
         for (int i = 0; i < MERGE_THREADS / 64; ++i) l_tot += part_s[i];
-        const long long q_row = b.cu_new_lens[r];
+        const long long q_row = safe_first_row(b, r, 1);
         const int head = kvh * G + row;
         ((__bf16*)a.out)[(q_row * b.num_q_heads + head) * D + ch] = (__bf16)(l_tot > 0.f ? acc / l_tot : 0.f);
         if (ch == 0 && a.lse != nullptr)

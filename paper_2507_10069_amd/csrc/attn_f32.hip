@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
     const int r = lo;
     const int j = t - b.cu_new_lens[r];
     const int P = b.prefix_lens[r];
-    const int len = a.causal ? P + j + 1 : P;
+    // (forced into what the page-table row can hold, whatever the arrays say: no access leaves the caller's buffers)
+    const int len = (int)min(max(a.causal ? (long long)P + j + 1 : (long long)P, 0ll), (long long)b.max_pages * b.page_size);
 
     const float* __restrict__ q = (const float*)a.q + ((long long)t * b.num_q_heads + h) * D;
     const float* __restrict__ kc = (const float*)a.k_cache;
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a)
         float s = -INFINITY;
         int my_page = 0;                                 // page of key base + lane; the value phase gets it by shuffle
         if (i < len) {
-            const long long page = my_page = pt[i >> pg_log2];
+            const long long page = my_page = min(max(pt[i >> pg_log2], 0), b.num_pages - 1);
             const float4* k4 = (const float4*)(kc + ((page * b.num_kv_heads + kvh) * ps + (i & (ps - 1))) * D);
             const float4* q4 = (const float4*)q;
             float dot = 0.f;

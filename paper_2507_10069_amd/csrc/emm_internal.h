@@ -19,6 +19,29 @@ struct BatchView {
     float softmax_scale;
 };
 
+// The batch's lengths as the kernels use them.  The arrays live in device memory, where the host cannot check
+// them; whatever they hold (a caller's bug, freed memory), the values below keep every address the kernels form
+// inside the caller's buffers.  A consistent batch passes through unchanged.
+//   new tokens of request r: 0 .. max_new_len, at most T, and (causal: they have slots) at most what a row of
+//   the page table can hold
+__device__ inline int safe_new_len(const BatchView& b, int r, bool causal)
+{
+    int n = min(max(b.new_lens[r], 0), min(b.max_new_len, b.total_new_tokens));
+    if (causal) n = (int)min((long long)n, (long long)b.max_pages * b.page_size);
+    return n;
+}
+//   cached tokens: what fits the page-table row next to n_slots more tokens (the new ones if causal, else 0)
+__device__ inline int safe_prefix_len(const BatchView& b, int r, int n_slots)
+{
+    const long long room = (long long)b.max_pages * b.page_size - n_slots;
+    return (int)min((long long)max(b.prefix_lens[r], 0), max(room, 0ll));
+}
+//   first packed row: such that n_new rows from it on lie inside [0, T)
+__device__ inline int safe_first_row(const BatchView& b, int r, int n_new)
+{
+    return min(max(b.cu_new_lens[r], 0), max(b.total_new_tokens - n_new, 0));
+}
+
 struct AttnArgs {
     BatchView b;
     const void* q;        // [T][H][d]

@@ -32,9 +32,12 @@ __global__ __launch_bounds__(64 * WAVES) void kv_scatter_kernel(BatchView b, con
         if (b.cu_new_lens[mid] <= t) lo = mid; else hi = mid;
     }
     const int r = lo;
-    const int pos = b.prefix_lens[r] + (t - b.cu_new_lens[r]);
+    const long long pos64 = (long long)b.prefix_lens[r] + (t - b.cu_new_lens[r]);
+    // inconsistent lengths or a corrupt table: drop the write, never stray
+    if (pos64 < 0 || pos64 >= (long long)b.max_pages * b.page_size) return;
+    const int pos = (int)pos64;
     const int page = b.page_table[(long long)r * b.max_pages + (pos >> (4 + b.page_shift))];
-    if (page < 0 || page >= b.num_pages) return;         // corrupt table: drop the write, never stray
+    if (page < 0 || page >= b.num_pages) return;
 
     const int token_chunks = b.num_kv_heads << row_shift;                 // chunks of the token's K (or V) row, all heads
     const long long src = (long long)t * token_chunks;
