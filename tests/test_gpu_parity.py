@@ -689,3 +689,37 @@ def test_error_codes_on_device():
     with pytest.raises(B.EmmError) as e:
         bad.scatter()
     assert e.value.status == B.EMM_ERR_UNSUPPORTED
+
+
+def test_two_streams_with_their_own_workspaces():
+    """The library keeps no state between calls: two batches stepped on two streams at the same time, each with
+    its own workspace, give the bits they give when stepped one after the other.  (Both streams have the default
+    priority.)"""
+    print("case two streams", flush=True)
+    bits = B.DeviceWorkload.to_numpy_bits
+    def build_a():
+        return W.build_workload("stream_a", "causal", "bf16", 1800, num_q_heads=28, num_kv_heads=4, head_dim=128,
+                                page_size=16, prefix_lens=[9000, 300, 5000], new_lens=[64, 200, 36])      # cut units, merge kernel
+    def build_b():
+        return W.build_workload("stream_b", "causal", "bf16", 1801, num_q_heads=32, num_kv_heads=8, head_dim=128,
+                                page_size=16, prefix_lens=[2100, 2200, 900, 40, 7000], new_lens=[1, 1, 1, 1, 1])   # decode pieces
+    ref_a, ref_b = _gpu_run(build_a()), _gpu_run(build_b())
+    want_a, want_b = bits(ref_a.out).copy(), bits(ref_b.out).copy()
+    dw_a, dw_b = B.DeviceWorkload(build_a()), B.DeviceWorkload(build_b())
+    torch.cuda.synchronize()
+    s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):                                  # the later rounds overwrite what the earlier ones wrote
+        dw_a.out.zero_()
+        dw_b.out.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s_a):
+            dw_a.step()
+        with torch.cuda.stream(s_b):
+            dw_b.step()
+        with torch.cuda.stream(s_a):
+            dw_a.attention()
+        with torch.cuda.stream(s_b):
+            dw_b.attention()
+        torch.cuda.synchronize()
+        assert bits(dw_a.out).tobytes() == want_a.tobytes()
+        assert bits(dw_b.out).tobytes() == want_b.tobytes()
