@@ -265,6 +265,29 @@ emm_status emm_validate_batch_host(const emm_batch *batch, const int32_t *host_p
                                    const int32_t *host_prefix_lens, const int32_t *host_new_lens,
                                    const int32_t *host_cu_new_lens, int causal);
 
+/*
+ * How emm_prefill_attn / emm_cross_attn would lay out an EMM_BF16 batch that is not a decode batch, from the
+ * scalar fields and a HOST copy of new_lens (diagnostics, sizing, tests; no GPU work).  The kernels deal the
+ * (request, KV head) pairs to the chip's 8 XCDs and cut each pair's query rows into work units of 256 rows
+ * (Section 3.3 prefill over cached prefixes; the decomposition is this library's).
+ *   fan             each pair is dealt to this many XCDs (1 unless the batch has fewer than 8 pairs)
+ *   cutting         1: units left over after an XCD's full rounds of 32 may be cut along the keys or halved
+ *   slots_per_xcd   workgroups per XCD that may hold a unit; grid = 8 * (slots_per_xcd + 31 if cutting)
+ *   units[x]        work units of XCD x
+ *   pieces[x]       pieces planned for each of its left-over units (1: none are cut)
+ *   uneven_k[x]     > 0: those pieces are a long and a short one, the cut at k / (k + 1) of the keys
+ *   rows_only[x]    1: the left-over units are halved along their rows, never cut along the keys
+ * with_workspace says whether the call would be given a workspace (without one nothing is cut).
+ * EMM_ERR_UNSUPPORTED unless the batch is EMM_BF16 with head_dim 128.
+ */
+typedef struct {
+    int32_t fan, n_row_tiles, pairs_per_xcd, cutting, uneven, slots_per_xcd;
+    int64_t grid;
+    int32_t units[8], pieces[8], uneven_k[8], rows_only[8];
+} emm_prefill_plan;
+emm_status emm_prefill_plan_host(const emm_batch *batch, const int32_t *host_new_lens, int with_workspace,
+                                 emm_prefill_plan *plan);
+
 const char *emm_status_string(emm_status status);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

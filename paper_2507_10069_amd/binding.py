@@ -22,7 +22,7 @@ EMM_F32, EMM_BF16 = 0, 1
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
            "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
            "emm_cross_attn_shared", "emm_decode_step", "emm_kv_pages_pack", "emm_kv_pages_unpack",
-           "emm_validate_batch_host", "emm_status_string", "emm_version"]
+           "emm_validate_batch_host", "emm_prefill_plan_host", "emm_status_string", "emm_version"]
 
 
 class EmmError(RuntimeError):
@@ -38,6 +38,13 @@ class emm_batch(ctypes.Structure):
                 ("max_new_len", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("reserved", ctypes.c_int32), ("page_table", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
                 ("new_lens", ctypes.c_void_p), ("cu_new_lens", ctypes.c_void_p)]
+
+
+class emm_prefill_plan(ctypes.Structure):
+    _fields_ = [("fan", ctypes.c_int32), ("n_row_tiles", ctypes.c_int32), ("pairs_per_xcd", ctypes.c_int32),
+                ("cutting", ctypes.c_int32), ("uneven", ctypes.c_int32), ("slots_per_xcd", ctypes.c_int32),
+                ("grid", ctypes.c_int64), ("units", ctypes.c_int32 * 8), ("pieces", ctypes.c_int32 * 8),
+                ("uneven_k", ctypes.c_int32 * 8), ("rows_only", ctypes.c_int32 * 8)]
 
 
 class emm_shared_prefix(ctypes.Structure):
@@ -88,6 +95,8 @@ def load() -> ctypes.CDLL:
     lib.emm_kv_pages_unpack.argtypes = [vp, vp, ctypes.c_int32, vp, vp, ctypes.c_int32, ctypes.c_int64, vp, vp, vp, vp]
     lib.emm_validate_batch_host.restype = ctypes.c_int
     lib.emm_validate_batch_host.argtypes = [bp, i32p, i32p, i32p, i32p, ctypes.c_int]
+    lib.emm_prefill_plan_host.restype = ctypes.c_int
+    lib.emm_prefill_plan_host.argtypes = [bp, i32p, ctypes.c_int, ctypes.POINTER(emm_prefill_plan)]
     lib.emm_status_string.restype = ctypes.c_char_p
     lib.emm_status_string.argtypes = [ctypes.c_int]
     lib.emm_version.restype = ctypes.c_int
@@ -124,6 +133,19 @@ def make_batch(*, num_reqs, num_q_heads, num_kv_heads, head_dim, page_size, num_
                       _ptr(page_table), _ptr(prefix_lens), _ptr(new_lens), _ptr(cu_new_lens))
     batch._keepalive = (page_table, prefix_lens, new_lens, cu_new_lens)
     return batch
+
+
+def emm_prefill_plan_host(batch: emm_batch, new_lens, with_workspace: bool = True) -> dict:
+    """new_lens: host int32 array.  Returns the plan's fields, the per-XCD ones as lists of 8."""
+    nl = np.ascontiguousarray(new_lens, dtype=np.int32)
+    plan = emm_prefill_plan()
+    st = load().emm_prefill_plan_host(ctypes.byref(batch), nl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                      int(with_workspace), ctypes.byref(plan))
+    if st != EMM_OK:
+        raise EmmError(st, "emm_prefill_plan_host")
+    out = {k: int(getattr(plan, k)) for k in ("fan", "n_row_tiles", "pairs_per_xcd", "cutting", "uneven", "slots_per_xcd", "grid")}
+    out.update({k: list(getattr(plan, k)) for k in ("units", "pieces", "uneven_k", "rows_only")})
+    return out
 
 
 def _check(status: int, where: str) -> None:

@@ -399,6 +399,30 @@ emm_status emm_validate_batch_host(const emm_batch* b, const int32_t* pt, const 
     return EMM_OK;
 }
 
+emm_status emm_prefill_plan_host(const emm_batch* b, const int32_t* new_lens, int with_workspace, emm_prefill_plan* plan)
+{
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    st = check_supported(b);
+    if (st != EMM_OK) return st;
+    if (b->dtype != EMM_BF16) return EMM_ERR_UNSUPPORTED;
+    if (plan == nullptr || (b->num_reqs > 0 && new_lens == nullptr)) return EMM_ERR_NULL;
+    *plan = emm_prefill_plan{};
+    if (b->num_reqs == 0 || b->total_new_tokens == 0) return EMM_OK;
+    int32_t shape[6];
+    long long grid = 0;
+    emm::attn_bf16_d128_plan_host(view_of(b), new_lens, with_workspace != 0, shape, &grid, plan->units, plan->pieces,
+                                  plan->uneven_k, plan->rows_only);
+    plan->fan = shape[0];
+    plan->n_row_tiles = shape[1];
+    plan->pairs_per_xcd = shape[2];
+    plan->cutting = shape[3];
+    plan->uneven = shape[4];
+    plan->slots_per_xcd = shape[5];
+    plan->grid = grid;
+    return EMM_OK;
+}
+
 const char* emm_status_string(emm_status s)
 {
     switch (s) {

@@ -46,6 +46,7 @@
 // bound by that port (about 49 cycles per MFMA), not by the matrix pipe.
 #include "attn_bf16_common.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace emm {
@@ -104,6 +105,7 @@ constexpr int CU_PER_XCD = 32;
 constexpr int MAX_PARTS = 32;                            // pieces per unit at most
 constexpr int PIECES_PER_XCD = 2 * CU_PER_XCD;           // tail units x pieces of an XCD: at most 32, or 2 x 30 (uneven cuts)
 constexpr int EXTRA_PER_XCD = CU_PER_XCD - 1;            // workgroups for pieces 1, 2, ... of an XCD's tail units
+constexpr int MERGE_PER_XCD = CU_PER_XCD;                // merge workgroups: tail units x shares never exceed 32
 constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
 constexpr int MIN_TILES_PER_PART_UNDERFILLED = 8;        // ... unless the compute units would stay idle otherwise
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 64;              // planning scans an XCD's pairs, one per lane of a wave
@@ -957,10 +959,10 @@ size_t attn_bf16_d128_workspace_bytes()
     return (size_t)NUM_XCD * PIECES_PER_XCD * PART_FLOATS * sizeof(float);
 }
 
-hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
+// The launch shape of a batch, from what the host knows: the scalar fields and whether there is a workspace.
+// `slots` is the number of workgroups per XCD that may hold units (the extra ones for pieces come on top).
+static void launch_shape(const BatchView& b, bool has_workspace, LaunchShape& L, long long& slots)
 {
-    const BatchView& b = a.b;
-    if (b.total_new_tokens == 0 || b.num_reqs == 0) return hipSuccess;
     const int G = b.num_q_heads / b.num_kv_heads;
     const long long max_rows = (long long)b.max_new_len * G;
     const long long n_pair_tiles = (max_rows + BR - 1) / BR;
@@ -970,12 +972,11 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     const long long n_pairs = n_real_pairs * fan;                        // sub-pairs
     const long long n_row_tiles = (n_pair_tiles + fan - 1) / fan;        // per sub-pair
     const long long pairs_per_xcd = (n_pairs + NUM_XCD - 1) / NUM_XCD;
-    LaunchShape L;
     L.n_row_tiles = (int)n_row_tiles;
     L.n_pairs = (int)n_pairs;
     L.pairs_per_xcd = (int)pairs_per_xcd;
     L.fan = fan;
-    L.split = (a.workspace != nullptr && pairs_per_xcd <= SPLIT_MAX_PAIRS_PER_XCD) ? 1 : 0;
+    L.split = (has_workspace && pairs_per_xcd <= SPLIT_MAX_PAIRS_PER_XCD) ? 1 : 0;
     L.uneven = 1;
     if (L.split && (long long)b.num_reqs * b.max_new_len == b.total_new_tokens) {
         // every request has max_new_len new tokens, so the host knows each XCD's unit count and can tell
@@ -997,7 +998,7 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
             any = any || split_factor((int)(units[x] % CU_PER_XCD), (int)(units[x] / CU_PER_XCD), L.uneven) > 1;
         if (!any) L.split = 0;
     }
-    long long slots = pairs_per_xcd * n_row_tiles;                       // one per row tile of the longest request, per pair
+    slots = pairs_per_xcd * n_row_tiles;                                 // one per row tile of the longest request, per pair
     if (L.split && fan == 1) {
         // With cutting, workgroup j of an XCD takes the XCD's unit j, so the grid only has to cover the units there
         // are.  An XCD holds at most ceil(Hkv / 8) pairs of a request, and the row tiles of all requests number at
@@ -1008,6 +1009,42 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
                                 ((long long)b.total_new_tokens * G / BR + b.num_reqs);
         slots = slots < bound ? slots : bound;
     }
+}
+
+// What the planner makes of a batch whose new-token counts are given as a host array: the launch shape and, per
+// XCD, the units, the pieces planned for each tail unit and the kind of cut (see emm_prefill_plan in emm.h).
+void attn_bf16_d128_plan_host(const BatchView& b, const int32_t* new_lens, bool has_workspace, int32_t* shape6, long long* grid,
+                              int32_t* units, int32_t* pieces, int32_t* uneven_k, int32_t* rows_only)
+{
+    LaunchShape L;
+    long long slots = 0;
+    launch_shape(b, has_workspace, L, slots);
+    const int G = b.num_q_heads / b.num_kv_heads;
+    shape6[0] = L.fan; shape6[1] = L.n_row_tiles; shape6[2] = L.pairs_per_xcd; shape6[3] = L.split; shape6[4] = L.uneven;
+    shape6[5] = (int32_t)slots;
+    *grid = NUM_XCD * (slots + (L.split ? EXTRA_PER_XCD : 0));
+    for (int x = 0; x < NUM_XCD; ++x) {
+        long long total = 0;
+        for (long long sp = x; sp < L.n_pairs; sp += NUM_XCD) {
+            const int r = (int)(sp / L.fan / b.num_kv_heads);
+            const int n = std::min(std::max(new_lens[r], 0), std::min(b.max_new_len, b.total_new_tokens));
+            total += sub_pair_tiles(n, G, L.fan, (int)sp);
+        }
+        const int rem = (int)(total % CU_PER_XCD), full = (int)(total / CU_PER_XCD);
+        units[x] = (int32_t)total;
+        pieces[x] = L.split ? split_factor(rem, full, L.uneven) : 1;
+        uneven_k[x] = (L.split && L.uneven) ? uneven_of(rem) : 0;
+        rows_only[x] = (L.split && rows_only_of(rem, full)) ? 1 : 0;
+    }
+}
+
+hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
+{
+    const BatchView& b = a.b;
+    if (b.total_new_tokens == 0 || b.num_reqs == 0) return hipSuccess;
+    LaunchShape L;
+    long long slots = 0;
+    launch_shape(b, a.workspace != nullptr, L, slots);
     const long long per_xcd = slots + (L.split ? EXTRA_PER_XCD : 0);
     const long long grid = NUM_XCD * per_xcd;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
@@ -1020,7 +1057,7 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     // no context of this batch is long enough for two pieces along the keys: left-over units can only have been
     // halved along their rows, which leaves nothing to merge
     if (((long long)b.max_pages * b.page_size + BC - 1) / BC < 2ll * MIN_TILES_PER_PART) return err;
-    hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * PIECES_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
+    hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * MERGE_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }
 

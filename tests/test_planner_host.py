@@ -1,0 +1,116 @@
+"""Host logic of the prefill launch (emm_prefill_plan_host): how a batch is dealt to the XCDs, how many work
+units each gets, and how the units left over after full rounds are cut -- against a model written out here in
+plain Python, and against the invariants the kernels rely on (every unit appears once; the extra workgroups,
+the workspace slots and the merge workgroups suffice).  No GPU."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from paper_2507_10069_amd import binding as B
+from paper_2507_10069_amd import workloads as W
+
+XCDS, CUS, ROWS = 8, 32, 256
+
+
+def _batch(H, Hkv, new, dtype="bf16", d=128):
+    return B.make_batch(num_reqs=len(new), num_q_heads=H, num_kv_heads=Hkv, head_dim=d, page_size=16, num_pages=1 << 20,
+                        max_pages_per_req=1 << 16, total_new_tokens=int(sum(new)), max_new_len=int(max(new)) if len(new) else 0,
+                        dtype=dtype, softmax_scale=0.1)
+
+
+def _model(H, Hkv, new):
+    """Units per XCD and pieces per left-over unit, from the description of the scheme alone."""
+    G = H // Hkv
+    pairs = len(new) * Hkv
+    fan = 1
+    while fan < XCDS and pairs * fan * 2 <= XCDS:
+        fan *= 2
+    units = [0] * XCDS
+    for p in range(pairs):
+        tiles = -(-new[p // Hkv] * G // ROWS)
+        for j in range(fan):                                   # sub-pair j of pair p takes row tiles j, j + fan, ...
+            units[(p * fan + j) % XCDS] += len(range(j, tiles, fan))
+    per_xcd = -(-pairs * fan // XCDS)
+    uniform = len(set(new)) == 1
+    cutting = per_xcd <= 64
+    uneven_ok = not (uniform and len(set(units)) == 1)
+    pieces, ks, halves = [], [], []
+    for u in units:
+        rem, full = u % CUS, u // CUS
+        k = -(-rem // (CUS - rem)) if (16 < rem <= 30 and uneven_ok) else 0
+        half = full > 0 and 12 < rem <= 16
+        if rem == 0:
+            p = 1
+        elif k or half:
+            p = 2
+        elif full == 0:
+            p = 1
+            while p < 32 and 2 * p * rem <= CUS:
+                p *= 2
+        else:
+            p = 1 if rem > 12 else 2 if rem > 8 else 4
+        pieces.append(p); ks.append(k); halves.append(int(half))
+    if uniform and cutting and all(p == 1 for p in pieces):
+        cutting = False                                        # the host knows that nothing will be cut
+    if not cutting:
+        pieces, ks, halves = [1] * XCDS, [0] * XCDS, [0] * XCDS
+    return fan, units, pieces, ks, halves, cutting
+
+
+def test_named_workloads():
+    cfg3 = W.config(3)
+    p = B.emm_prefill_plan_host(_batch(28, 4, cfg3.new_lens.tolist()), cfg3.new_lens)
+    assert p["units"] == [56] * 8 and p["cutting"] == 0 and p["grid"] == 448          # two rounds, the second of 24: not cut
+    one = B.emm_prefill_plan_host(_batch(28, 4, [36]), [36])                            # a lone unit on every other XCD
+    assert one["fan"] == 2 and one["units"] == [1, 0] * 4 and one["pieces"] == [32, 1] * 4 and one["grid"] == 8 * (1 + 31)
+    cfg5 = W.config(5)
+    p5 = B.emm_prefill_plan_host(_batch(32, 8, cfg5.new_lens.tolist()), cfg5.new_lens)
+    want = sum(-(-int(n) * 4 // ROWS) for n in cfg5.new_lens)                           # every XCD holds one KV head of every request
+    assert p5["units"] == [want] * 8 and p5["cutting"] == 1
+    no_ws = B.emm_prefill_plan_host(_batch(28, 4, [36]), [36], with_workspace=False)
+    assert no_ws["cutting"] == 0 and no_ws["pieces"] == [1] * 8 and no_ws["grid"] == 8
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_batches_match_model_and_keep_invariants(seed):
+    rng = np.random.default_rng(300 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8, 16]))
+    G = int(rng.choice([1, 2, 4, 7, 8]))
+    n_req = int(rng.choice([1, 1, 2, 3, 5, 8, 16, 33, 70]))
+    top = int(rng.choice([1, 3, 40, 300, 2100]))
+    new = [int(x) for x in rng.integers(0, top + 1, n_req)]
+    if rng.random() < 0.25:
+        new = [top] * n_req                                    # a uniform batch
+    if sum(new) == 0:
+        new[0] = top
+    H = Hkv * G
+    p = B.emm_prefill_plan_host(_batch(H, Hkv, new), new)
+    fan, units, pieces, ks, halves, cutting = _model(H, Hkv, new)
+    assert (p["fan"], p["units"], p["cutting"]) == (fan, units, int(cutting)), (new, p)
+    assert (p["pieces"], p["uneven_k"], p["rows_only"]) == (pieces, ks, halves), (new, p)
+    assert sum(p["units"]) == sum(-(-n * G // ROWS) for n in new) * Hkv              # every row tile of every pair, once
+    assert p["grid"] == XCDS * (p["slots_per_xcd"] + (31 if p["cutting"] else 0))
+    for x in range(XCDS):
+        rem = p["units"][x] % CUS
+        assert p["units"][x] <= p["slots_per_xcd"]                                     # a slot for every unit
+        assert rem * (p["pieces"][x] - 1) <= 31                                        # extra workgroups for pieces 1, 2, ...
+        assert rem * p["pieces"][x] <= 64                                              # workspace slots of the XCD
+        shares = 1 if p["uneven_k"][x] else p["pieces"][x]
+        assert p["pieces"][x] == 1 or rem * shares <= 32                               # merge workgroups of the XCD
+        assert (p["uneven_k"][x] > 0) <= (16 < rem <= 30)
+
+
+def test_argument_errors():
+    lib = B.load()
+    import ctypes
+    plan = B.emm_prefill_plan()
+    ok = (ctypes.c_int32 * 2)(5, 5)
+    assert lib.emm_prefill_plan_host(None, ok, 1, ctypes.byref(plan)) == B.EMM_ERR_NULL
+    b = _batch(8, 2, [5, 5])
+    assert lib.emm_prefill_plan_host(ctypes.byref(b), None, 1, ctypes.byref(plan)) == B.EMM_ERR_NULL
+    assert lib.emm_prefill_plan_host(ctypes.byref(b), ok, 1, None) == B.EMM_ERR_NULL
+    f32 = _batch(8, 2, [5, 5], dtype="f32", d=64)
+    assert lib.emm_prefill_plan_host(ctypes.byref(f32), ok, 1, ctypes.byref(plan)) == B.EMM_ERR_UNSUPPORTED
+    empty = _batch(8, 2, [])
+    assert lib.emm_prefill_plan_host(ctypes.byref(empty), None, 1, ctypes.byref(plan)) == B.EMM_OK and plan.grid == 0
