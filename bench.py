@@ -421,7 +421,10 @@ def main():
             m, am, sm = time_workload(d, 30, 5)
             others[w.name] = {"ms_per_step": m, "attention_ms": am, "scatter_ms": sm,
                               "tflops": w.attention_flops() / (m * 1e-3) / 1e12,
+                              "attention_tflops": w.attention_flops() / (am * 1e-3) / 1e12,
                               "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
+            if w.dtype == "bf16":
+                others[w.name]["frac_bf16_mfma_peak"] = others[w.name]["attention_tflops"] / BF16_MFMA_PEAK_TFLOPS
             log("workload %s: %s" % (w.name, others[w.name]))
             del d
         for name in W.SUFFIX_CONFIGS:                    # short suffixes after a large cache hit
