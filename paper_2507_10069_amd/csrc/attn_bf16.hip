@@ -107,7 +107,8 @@ constexpr int PIECES_PER_XCD = 2 * CU_PER_XCD;           // tail units x pieces 
 constexpr int EXTRA_PER_XCD = CU_PER_XCD - 1;            // workgroups for pieces 1, 2, ... of an XCD's tail units
 constexpr int MERGE_PER_XCD = CU_PER_XCD;                // merge workgroups: tail units x shares never exceed 32
 constexpr int MIN_TILES_PER_PART = 16;                   // shorter pieces cost more (prologue, merge) than they gain: measured
-constexpr int MIN_TILES_PER_PART_UNDERFILLED = 8;        // ... unless the compute units would stay idle otherwise
+constexpr int MIN_TILES_PER_PART_UNDERFILLED = 2;        // ... unless the compute units would stay idle otherwise (swept: 1 .. 12)
+constexpr int MIN_UNIT_TILES_UNDERFILLED = 24;           // ... and the unit is long enough to pay for the merge launch (measured)
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 64;              // planning scans an XCD's pairs, one per lane of a wave
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
 
@@ -184,6 +185,7 @@ __device__ inline bool cuttable(int n_tiles, int parts, int limit_min, int min_t
 // that it can be cut into (1: not at all).  Every workgroup concerned with the unit finds the same number.
 __device__ inline int pieces_cut(int n_tiles, int parts, int limit_min, int min_tiles)
 {
+    if (n_tiles < MIN_UNIT_TILES_UNDERFILLED) min_tiles = MIN_TILES_PER_PART;
     while (parts > 1 && !cuttable(n_tiles, parts, limit_min, min_tiles)) parts >>= 1;
     // two short pieces are no better than two row halves, which need no merge: pieces shorter than the usual
     // minimum only when there are at least four of them
@@ -1054,9 +1056,12 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
         hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, L);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || !L.split) return err;
-    // no context of this batch is long enough for two pieces along the keys: left-over units can only have been
-    // halved along their rows, which leaves nothing to merge
-    if (((long long)b.max_pages * b.page_size + BC - 1) / BC < 2ll * MIN_TILES_PER_PART) return err;
+    // no context of this batch is long enough to be cut along the keys (two pieces of the usual minimum, or four
+    // short ones on an under-filled XCD): left-over units can only have been halved along their rows, which
+    // leaves nothing to merge
+    constexpr long long MIN_CUT_TILES = 2 * MIN_TILES_PER_PART < MIN_UNIT_TILES_UNDERFILLED ? 2 * MIN_TILES_PER_PART : MIN_UNIT_TILES_UNDERFILLED;
+    static_assert(4 * MIN_TILES_PER_PART_UNDERFILLED <= MIN_UNIT_TILES_UNDERFILLED, "short pieces come four or more at a time");
+    if (((long long)b.max_pages * b.page_size + BC - 1) / BC < MIN_CUT_TILES) return err;
     hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * MERGE_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }

@@ -126,7 +126,8 @@ def test_ragged_cross_sweep():
 # 256-row tile of one (request, KV head) pair; pairs are dealt to the 8 XCDs; the units an XCD has left over
 # after its full rounds of 32 are cut into 4 pieces (1..8 left over) or 2 (9..12) when every piece gets at least
 # 16 key tiles and starts below the diagonal; an XCD without a full round cuts into as many pieces as fill it,
-# up to 32, of at least 8 key tiles.
+# up to 32, of at least 2 key tiles, if the unit has 24 key tiles or more (four or more such pieces: two short ones
+# are no better than two row halves).
 CUT_CASES = [
     # name, kind, H, Hkv, prefix lens, new lens
     ("cut4_causal", "causal", 28, 4, [5000], [64]),                 # 1 unit per XCD, planned for 32 pieces; 80 tiles give 8 of 10
@@ -189,9 +190,9 @@ def test_cut_units_parity(name, kind, H, Hkv, prefix, new):
 @pytest.mark.parametrize("kind,n_req", [("causal", 1), ("causal", 2), ("cross", 1), ("cross", 3)])
 def test_cut_thresholds_sweep(kind, n_req):
     """Contexts whose key-tile counts sit on and around every threshold of the cutting rule (pieces of at least
-    8 or 16 tiles, 2 .. 32 of them), with the page table exactly as wide as the context needs: one and two
+    2 or 16 tiles, 2 .. 32 of them), with the page table exactly as wide as the context needs: one and two
     requests, so that an XCD holds one unit (32 pieces planned) or two (16); three for cross-attention (8)."""
-    for tiles in (15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257):
+    for tiles in (7, 8, 9, 15, 16, 17, 23, 24, 25, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257):
         for slack in (0, 1, 63):                           # the last tile full, one key short, one key only
             ctx = tiles * 64 - slack
             new = 3
