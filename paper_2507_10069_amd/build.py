@@ -45,22 +45,5 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
-def build_microbenchmark(verbose: bool = False) -> list:
-    """Compiles the stand-alone microbenchmarks (executables; the library does not use them)."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    exes = []
-    for name in ("mfma_lds_rates", "valu_issue_costs", "hbm_read_rates"):
-        exe = os.path.join(OBJ_DIR, name)
-        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-o", exe, os.path.join(CSRC, name + ".hip")]
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("hipcc failed for %s.hip:\n%s" % (name, res.stderr))
-        if verbose:
-            print("built", exe)
-        exes.append(exe)
-    return exes
-
-
 if __name__ == "__main__":
     build(verbose=True, extra_flags=sys.argv[1:])

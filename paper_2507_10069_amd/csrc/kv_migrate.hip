@@ -65,16 +65,17 @@ __global__ __launch_bounds__(THREADS) void kv_pages_kernel(unsigned char* __rest
                 unsigned char* pool = off < page_bytes ? kp + off : vp + (off - page_bytes);
                 *(uint4*)(UNPACK ? pool : sp + off) = w[u];
                 const unsigned words[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
-                unsigned s_all = 0, weighted = 0;                         // of the 16 bytes; both far below 2^32
+                unsigned s_all = 0;                                       // of the 16 bytes: at most 4080
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const unsigned s = __builtin_amdgcn_udot4(words[j], 0x01010101u, 0u, false);   // d0 + d1 + d2 + d3
                     const unsigned t = __builtin_amdgcn_udot4(words[j], 0x03020100u, 0u, false);   // d1 + 2 d2 + 3 d3
                     s_all += s;
-                    weighted += (unsigned)(n - off - 4 * j) * s - t;      // (n - position) <= 2^21, s <= 1020
+                    // one word's term fits 32 bits ((n - position) <= 2^21, s <= 1020: below 2^31.1), the four of a
+                    // chunk together need not (pages above 512 KiB), so each goes into the 64-bit sum by itself
+                    sum_w += (unsigned)(n - off - 4 * j) * s - t;
                 }
                 sum_d += s_all;
-                sum_w += weighted;
             }
         }
     }

@@ -2,8 +2,8 @@
 
 Bars: the KV scatter is bit-exact over the whole pool; bf16 attention outputs are within max-abs 2e-2
 and mean-abs 2e-3 of the oracle (bf16 inputs, fp32 accumulation); the fp32 configuration is held to
-max-abs 1e-4.  Sizes the oracle finishes in seconds are compared element by element; the full-size
-workloads are compared on sampled query tokens (all heads, all channels)."""
+max-abs 1e-4.  Every workload is compared element by element, the three large ones at full size too (the
+oracle takes 15 to 30 s for each); a quick variant compares them on sampled query tokens."""
 import numpy as np
 import pytest
 import torch
@@ -78,6 +78,18 @@ def test_full_size_sampled_parity(cfg, n):
     dw = _gpu_run(wl)
     tokens = _sample_tokens(wl, n, seed=cfg)
     print("   errors (max, mean, lse):", _compare(wl, dw, tokens), flush=True)
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_size_exhaustive_parity(cfg):
+    """Every output element of the three large workloads, at the sizes and in the launch configuration bench.py
+    times, against the oracle (which takes 15 to 30 s per workload on the host cores): the max-abs / mean-abs bars
+    are stated over all T x H x d elements of a workload, and the pools are compared byte for byte."""
+    print("case full exhaustive cfg=%d" % cfg, flush=True)
+    wl = W.config(cfg, 1)
+    dw = _gpu_run(wl)
+    print("   errors over all %d x %d x %d elements (max, mean, lse):" % (wl.total_new_tokens, wl.num_q_heads, wl.head_dim),
+          _compare(wl, dw), flush=True)
 
 
 @pytest.mark.parametrize("name", W.SUFFIX_CONFIGS)
@@ -587,6 +599,40 @@ def test_kv_page_migration_is_exact_and_checksummed():
     B.emm_decode_attn(batch, dw.q, kd, vd, out, None, ws)
     torch.cuda.synchronize()
     assert B.DeviceWorkload.to_numpy_bits(out).tobytes() == src_out
+
+
+def test_kv_page_checksum_of_the_largest_page():
+    """Pages of 1 MiB per pool (the largest admitted: e.g. 16 KV heads x 256 tokens x 128 channels in bf16) filled
+    with large byte values: the position-weighted sum of a 16-byte chunk alone passes 2^32 there.  Bytes and
+    Adler-32 values against the reference, pack and unpack."""
+    from oracle import kv_migrate_model as KM
+    print("case kv page checksum, 1 MiB pages", flush=True)
+    page_bytes = 1 << 20
+    rng = np.random.default_rng(12)
+    kc = rng.integers(200, 256, (3, page_bytes), dtype=np.uint8)
+    vc = rng.integers(0, 256, (3, page_bytes), dtype=np.uint8)
+    kc[1, :] = 0xFF
+    vc[1, :] = 0xFF
+    kc[2, :] = 0
+    vc[2, :] = 0
+    kc[2, :4096] = 0xFF
+    k_d, v_d = torch.from_numpy(kc).to("cuda:0"), torch.from_numpy(vc).to("cuda:0")
+    ids = np.array([2, 0, 1], np.int32)
+    ids_d = torch.from_numpy(ids).to("cuda:0")
+    staging = torch.zeros(3 * 2 * page_bytes, dtype=torch.uint8, device="cuda:0")
+    sums = torch.zeros(3, dtype=torch.int32, device="cuda:0")
+    B.emm_kv_pages_pack(k_d, v_d, 3, page_bytes, ids_d, 3, staging, sums)
+    ref_staging, ref_sums = KM.pack(kc, vc, ids)
+    assert staging.cpu().numpy().tobytes() == ref_staging.tobytes()
+    assert (sums.cpu().numpy().view(np.uint32) == ref_sums).all(), (sums.cpu().numpy().view(np.uint32), ref_sums)
+    k2, v2 = torch.zeros_like(k_d), torch.zeros_like(v_d)
+    sums2 = torch.zeros_like(sums)
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    dst = np.array([1, 2, 0], np.int32)
+    B.emm_kv_pages_unpack(staging, torch.from_numpy(dst).to("cuda:0"), 3, k2, v2, 3, page_bytes, sums2, sums, bad)
+    k_ref, v_ref, ref_sums2 = KM.unpack(ref_staging, dst, np.zeros_like(kc), np.zeros_like(vc))
+    assert (sums2.cpu().numpy().view(np.uint32) == ref_sums2).all() and int(bad.item()) == 0
+    assert k2.cpu().numpy().tobytes() == k_ref.tobytes() and v2.cpu().numpy().tobytes() == v_ref.tobytes()
 
 
 def test_f32_head_dim_128_and_cross():

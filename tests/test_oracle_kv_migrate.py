@@ -31,6 +31,31 @@ def test_checksum_is_adler32():
         assert int(s) == (b << 16 | a)
 
 
+def test_checksum_of_a_large_page_with_high_bytes():
+    """A staging page of 2 MiB (the largest the library admits: 1 MiB per pool) whose bytes are all large: the
+    position-weighted sum passes 2^32 many times over.  Closed form in exact integers: for n bytes d_i at positions
+    i = 0 .. n-1, A = 1 + sum d_i and B = n + sum (n - i) d_i, both mod 65521 (RFC 1950 written as sums)."""
+    n_half = 1 << 20
+    rng = np.random.default_rng(5)
+    for fill in ("ff", "random_high", "ff_head"):
+        if fill == "ff":
+            data = np.full(2 * n_half, 0xFF, np.uint8)
+        elif fill == "random_high":
+            data = rng.integers(200, 256, 2 * n_half, dtype=np.uint8)
+        else:
+            data = np.zeros(2 * n_half, np.uint8)
+            data[:4096] = 0xFF
+        k = data[:n_half].reshape(1, n_half)
+        v = data[n_half:].reshape(1, n_half)
+        _, sums = M.pack(k, v, [0])
+        n = 2 * n_half
+        d = data.astype(object)                              # Python integers: no overflow anywhere
+        a = (1 + int(d.sum())) % 65521
+        weights = np.arange(n, 0, -1).astype(object)
+        b = (n + int((weights * d).sum())) % 65521
+        assert int(sums[0]) == (b << 16 | a), fill
+
+
 def test_round_trip_is_exact_and_touches_nothing_else():
     rng = np.random.default_rng(4)
     kc, vc = _pools(rng, 12, 4, 128)
