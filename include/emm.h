@@ -138,6 +138,25 @@ emm_status emm_decode_attn(const emm_batch *batch, const void *q, const void *k_
                            size_t workspace_bytes, void *hip_stream);
 
 /*
+ * emm_decode_attn for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels and the same results, bit for bit, with the piece
+ * records in a fixed array of EMM_DECODE_STATIC_SCRATCH_BYTES inside the library's device image instead of a
+ * caller's workspace.  The call allocates and frees nothing.  Every GPU the library is used on holds its own
+ * copy of the array until the process ends; its address is looked up on the first call on a device, so the
+ * device of `hip_stream` must be the current device.
+ *   bf16 decode-shaped batches only (max_new_len <= 1, H / Hkv <= 16), else EMM_ERR_INVALID_ARG /
+ *   EMM_ERR_UNSUPPORTED; a batch for which emm_prefill_attn_workspace_size exceeds
+ *   EMM_DECODE_STATIC_SCRATCH_BYTES is refused with EMM_ERR_WORKSPACE before anything is launched (64 requests
+ *   x 4 KV heads x 8192 tokens need 12.2 MiB).
+ * All calls on one GPU share that GPU's array: calls that may overlap there (different streams, several
+ * threads) race on it and must be ordered by the caller.  Nothing in the array has to start at zero; a call
+ * overwrites what it later reads.
+ */
+#define EMM_DECODE_STATIC_SCRATCH_BYTES (16u << 20)
+emm_status emm_decode_attn_static(const emm_batch *batch, const void *q, const void *k_cache,
+                                  const void *v_cache, void *out, float *lse, void *hip_stream);
+
+/*
  * Decode step with shared prefixes (Section 3.3: requests repeat system prompts and images, so in a decode
  * batch several requests hold the SAME physical pages at the head of their page tables; Section 2.2: the
  * step is bound by reading K/V).  A unit is a run of consecutive requests of the batch together with the

@@ -18,9 +18,10 @@ LIB_PATH = os.path.join(HERE, "libemm.so")
 
 EMM_OK, EMM_ERR_NULL, EMM_ERR_INVALID_ARG, EMM_ERR_UNSUPPORTED, EMM_ERR_WORKSPACE, EMM_ERR_LAUNCH = range(6)
 EMM_F32, EMM_BF16 = 0, 1
+EMM_DECODE_STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
-           "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
+           "emm_decode_attn_static", "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
            "emm_cross_attn_shared", "emm_decode_step", "emm_kv_pages_pack", "emm_kv_pages_unpack",
            "emm_validate_batch_host", "emm_prefill_plan_host", "emm_status_string", "emm_version"]
 
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.emm_decode_attn_static.restype = ctypes.c_int
+    lib.emm_decode_attn_static.argtypes = [bp, vp, vp, vp, vp, vp, vp]
     lib.emm_decode_attn_shared_workspace_size.restype = ctypes.c_int
     lib.emm_decode_attn_shared_workspace_size.argtypes = [bp, ctypes.POINTER(emm_shared_prefix), ctypes.POINTER(ctypes.c_size_t)]
     lib.emm_decode_attn_shared.restype = ctypes.c_int
@@ -189,6 +192,11 @@ def emm_cross_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, workspa
 
 def emm_decode_attn(batch: emm_batch, q, k_cache, v_cache, out, lse=None, workspace=None, stream=None) -> None:
     _attn("emm_decode_attn", batch, q, k_cache, v_cache, out, lse, workspace, stream)
+
+
+def emm_decode_attn_static(batch: emm_batch, q, k_cache, v_cache, out, lse=None, stream=None) -> None:
+    _check(load().emm_decode_attn_static(ctypes.byref(batch), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out),
+                                         _ptr(lse), _stream(stream)), "emm_decode_attn_static")
 
 
 def emm_decode_attn_shared_workspace_size(batch: emm_batch, shared: emm_shared_prefix) -> int:

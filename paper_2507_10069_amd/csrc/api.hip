@@ -81,7 +81,7 @@ emm::SharedPrefixView shared_view_of(const emm_shared_prefix* sp)
 emm_status attention(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache, void* out,
                      float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, int causal,
                      const emm_shared_prefix* sp = nullptr, const void* k_new = nullptr, const void* v_new = nullptr,
-                     bool fused = false)
+                     bool fused = false, bool static_scratch = false)
 {
     emm_status st = check_scalars(b);
     if (st != EMM_OK) return st;
@@ -96,6 +96,14 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     st = sp != nullptr ? emm_decode_attn_shared_workspace_size(b, sp, &need)
                        : emm_prefill_attn_workspace_size(b, &need);
     if (st != EMM_OK) return st;
+    if (static_scratch) {
+        // the decode kernels with the library's own fixed array in place of a workspace
+        if (b->dtype != EMM_BF16 || !emm::attn_bf16_decode_applies(view_of(b))) return EMM_ERR_UNSUPPORTED;
+        if (need > emm::attn_bf16_decode_static_scratch_bytes()) return EMM_ERR_WORKSPACE;
+        workspace = nullptr;
+        workspace_bytes = need;
+        need = 0;
+    }
     if (sp != nullptr && sp->num_units > 0 && (sp->unit_first_req == nullptr || sp->unit_num_reqs == nullptr || sp->unit_shared_len == nullptr ||
                           sp->req_unit == nullptr || sp->req_shared_len == nullptr))
         return EMM_ERR_NULL;
@@ -126,7 +134,9 @@ emm_status attention(const emm_batch* b, const void* q, const void* k_cache, con
     args.v_new = v_new;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err;
-    if (sp != nullptr) {
+    if (static_scratch) {
+        err = emm::launch_attn_bf16_decode_static(args, stream);
+    } else if (sp != nullptr) {
         const emm::SharedPrefixView sv = shared_view_of(sp);
         err = fused ? emm::launch_attn_bf16_decode_step(args, sv, stream)
                     : emm::launch_attn_bf16_decode_shared(args, sv, stream);
@@ -187,6 +197,14 @@ emm_status emm_decode_attn(const emm_batch* b, const void* q, const void* k_cach
 {
     if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
     return attention(b, q, k_cache, v_cache, out, lse, workspace, workspace_bytes, hip_stream, 1);
+}
+
+emm_status emm_decode_attn_static(const emm_batch* b, const void* q, const void* k_cache, const void* v_cache,
+                                  void* out, float* lse, void* hip_stream)
+{
+    static_assert(EMM_DECODE_STATIC_SCRATCH_BYTES == (16u << 20), "the header states the size of the fixed array");
+    if (b != nullptr && b->max_new_len > 1) return EMM_ERR_INVALID_ARG;
+    return attention(b, q, k_cache, v_cache, out, lse, nullptr, 0, hip_stream, 1, nullptr, nullptr, nullptr, false, true);
 }
 
 emm_status emm_decode_attn_shared_workspace_size(const emm_batch* b, const emm_shared_prefix* sp, size_t* bytes)

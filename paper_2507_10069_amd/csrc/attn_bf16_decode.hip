@@ -32,6 +32,8 @@
 // the pool when it is done, so a decode step is one launch less than scatter + attention.
 #include "attn_bf16_common.h"
 
+#include <mutex>
+
 namespace emm {
 
 namespace {
@@ -558,6 +560,47 @@ hipError_t launch_decode(const AttnArgs& a, const SharedPrefixView& sv, hipStrea
 
 hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream)
 {
+    return launch_decode<false, false>(a, SharedPrefixView{}, stream);
+}
+
+// ---- The same launch for callers that cannot allocate (code under HIP graph capture, serving loops, harnesses
+// that forbid hipMalloc): the piece records go to a fixed array in the library's own device image instead of a
+// workspace of the caller's.  Every GPU the library runs on holds the array (EMM_DECODE_STATIC_SCRATCH_BYTES) until the
+// process ends, at an address of its own, which is looked up once per device with that device current.  In host
+// code the array's name is only a handle for that lookup, never a device address: kernels get the looked-up pointer.
+namespace {
+
+constexpr size_t STATIC_SCRATCH_BYTES = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* scratch_ptr[MAX_DEVICES];                              // per device; nullptr until first use there
+std::mutex scratch_lock;
+
+}  // namespace
+
+size_t attn_bf16_decode_static_scratch_bytes() { return STATIC_SCRATCH_BYTES; }
+
+hipError_t launch_attn_bf16_decode_static(AttnArgs a, hipStream_t stream)
+{
+    if (attn_bf16_decode_workspace_bytes(a.b) > STATIC_SCRATCH_BYTES) return hipErrorInvalidValue;
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> guard(scratch_lock);
+        if (scratch_ptr[dev] == nullptr) {
+            err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (err != hipSuccess) return err;
+            if (ptr == nullptr) return hipErrorInvalidSymbol;
+            scratch_ptr[dev] = ptr;
+        }
+        ptr = scratch_ptr[dev];
+    }
+    // The kernels write every record they later read (no counters or flags, nothing that must start at zero), so
+    // what an earlier call left in the array does not matter.
+    a.workspace = ptr;
     return launch_decode<false, false>(a, SharedPrefixView{}, stream);
 }
 

@@ -81,6 +81,10 @@ void attn_bf16_d128_plan_host(const BatchView& b, const int32_t* new_lens, bool 
 bool attn_bf16_decode_applies(const BatchView& b);
 size_t attn_bf16_decode_workspace_bytes(const BatchView& b);
 hipError_t launch_attn_bf16_decode(const AttnArgs& a, hipStream_t stream);
+// the same with the piece records in the library's own fixed device array (no workspace of the caller's); fails with
+// hipErrorInvalidValue when the batch needs more than attn_bf16_decode_static_scratch_bytes()
+size_t attn_bf16_decode_static_scratch_bytes();
+hipError_t launch_attn_bf16_decode_static(AttnArgs a, hipStream_t stream);
 // the same with shared-prefix units (sv.num_units >= 1)
 size_t attn_bf16_decode_shared_workspace_bytes(const BatchView& b, const SharedPrefixView& sv);
 hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream);
