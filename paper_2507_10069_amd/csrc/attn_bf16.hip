@@ -57,15 +57,38 @@ using namespace bf16attn;
 
 constexpr int BR = 256;           // rows per workgroup
 constexpr int PF_DIST = 2;          // MFMA operands are read from LDS this many slices ahead of their use
+constexpr int SOFTMAX_SLICES = 28;  // of an iteration's 32 one-MFMA slices, the first this many carry the softmax arithmetic
+constexpr float LAG_LIMIT = 1048576.f;      // 2^20: a tile's row sum beyond this raises the row's reference exponent
+constexpr float OVERFLOW_LIMIT = 1.329228e36f;    // 2^120: a row sum at or beyond this (or NaN) at the end of a unit means
+                                            // that weights overflowed on the way; the unit is then done again with true maxima
+constexpr int VOTE_OFFSET = 2 * NBUF * KV_BYTES - 64;   // LDS bytes of the 8 waves' overflow votes: the end of the rings,
+                                            // clear of the output staging area at their start
 constexpr int OUT_STRIDE = 272;     // bytes between output rows staged in LDS: 256 + 16, which spreads the banks
 
-// Identity the optimiser cannot see through.  Inside the main loop, addresses derived from a per-lane
-// base by one XOR or add are recomputed from such a copy every iteration; hoisted out of the loop as
-// invariants they would cost a dozen registers the loop does not have.
-__device__ inline int opaque(int x)
+// Inside the main loop, addresses derived from a per-lane base by one XOR or add are recomputed every
+// iteration: hoisted out of the loop as invariants they would cost a dozen registers the loop does not have.
+// Written as volatile assembly, which the optimiser neither hoists nor merges, they cost the one instruction
+// and no copy of the base.  IMM: an inline constant or 32-bit literal.
+template <int IMM>
+__device__ inline int xor_here(int x)
 {
-    asm volatile("" : "+v"(x));
-    return x;
+    if constexpr (IMM == 0) return x;
+    int r;
+    asm volatile("v_xor_b32_e32 %0, %1, %2" : "=v"(r) : "i"(IMM), "v"(x));
+    return r;
+}
+template <int IMM>
+__device__ inline int add_here(int x)
+{
+    int r;
+    asm volatile("v_add_u32_e32 %0, %1, %2" : "=v"(r) : "i"(IMM), "v"(x));
+    return r;
+}
+__device__ inline int xor_add_here(int x, int x_imm, int add)      // (x ^ x_imm) + add; x_imm an inline constant
+{
+    int r;
+    asm volatile("v_xad_u32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "i"(x_imm), "v"(add));
+    return r;
 }
 
 // Ties a value to the place in the instruction stream where it is written: without it the optimiser
@@ -111,6 +134,15 @@ constexpr int MIN_TILES_PER_PART_UNDERFILLED = 2;        // ... unless the compu
 constexpr int MIN_UNIT_TILES_UNDERFILLED = 24;           // ... and the unit is long enough to pay for the merge launch (measured)
 constexpr int SPLIT_MAX_PAIRS_PER_XCD = 64;              // planning scans an XCD's pairs, one per lane of a wave
 constexpr int PART_FLOATS = (64 + 2) * NTHREADS;         // per thread: 64 accumulator values, m, l
+// A build with -DEMM_TIMELINE (python -m paper_2507_10069_amd.build --timeline -> libemm_timeline.so) makes every
+// workgroup of the prefill kernel leave a 64-byte record of when and where it ran in the first TIMELINE_BYTES of
+// the workspace; bench.py --timeline reads them.  The regular build has none of it.
+#ifdef EMM_TIMELINE
+constexpr int TIMELINE_RECORDS = 16384;
+constexpr size_t TIMELINE_BYTES = (size_t)TIMELINE_RECORDS * 64;
+#else
+constexpr size_t TIMELINE_BYTES = 0;
+#endif
 
 // With fewer than 8 (request, KV head) pairs some XCDs would get no work, so each pair is dealt to `fan`
 // XCDs: sub-pair pair * fan + j owns the row tiles j, j + fan, j + 2 fan, ...  "Pair" below means sub-pair.
@@ -284,13 +316,26 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
 // workspace of pieces: [xcd][tail slot x planned pieces per unit + piece][66][512] floats
 __device__ inline float* part_base(void* workspace, int xcd, int slot, int parts, int part)
 {
-    return (float*)workspace + (size_t)(xcd * PIECES_PER_XCD + slot * parts + part) * PART_FLOATS;
+    return (float*)((unsigned char*)workspace + TIMELINE_BYTES) + (size_t)(xcd * PIECES_PER_XCD + slot * parts + part) * PART_FLOATS;
 }
 
+struct KernArgs {
+    AttnArgs a;
+    LaunchShape L;
+};
+typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+
+// One work item -- a unit, or one piece of a cut unit -- from its plan to its output rows (or its record in the
+// workspace), by the whole workgroup.  CAREFUL = false is the fast way described at the top; if some row's weights
+// overflowed on the way (see OVERFLOW_LIMIT) it writes nothing and hands the item to the CAREFUL = true
+// instantiation, which takes the true running maximum before every tile's exponentials and cannot overflow.  `smem`: the 128 KB of LDS of the workgroup, K ring, then V ring.
 template <bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a, LaunchShape L)
+__device__ void attend_unit_carefully(unsigned long long kernargs, int xcd, int in_xcd, lds_bytes lds);
+
+template <bool CAUSAL, bool CAREFUL>
+__device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, const int xcd, const int in_xcd, UnitPlan plan,
+                                   unsigned char* smem)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * KV_BYTES];   // K ring, then V ring
     constexpr int V_SM = NBUF * KV_BYTES;                    // byte offset of the V buffers
 
     const BatchView& b = a.b;
@@ -301,9 +346,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     // stream the same pages through its L2.  plan_unit() says which unit, and which part of its key range,
     // this workgroup does.
     const int G = b.num_q_heads / b.num_kv_heads;
-    const int xcd = blockIdx.x % NUM_XCD, in_xcd = blockIdx.x / NUM_XCD;
-    UnitPlan plan = plan_unit(b, G, L, xcd, in_xcd);
-    if (plan.pair < 0) return;
+#ifdef EMM_TIMELINE
+    const long long tl_t0 = __builtin_amdgcn_s_memrealtime();            // 100 MHz, the same on every compute unit
+    const long long tl_c0 = __builtin_readcyclecounter();                // shader clock of this compute unit
+#endif
     const int pair = plan.pair, tile = plan.tile;
     const int kvh = pair % b.num_kv_heads;
     const int r = pair / b.num_kv_heads;
@@ -417,15 +463,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     };
     auto load_k = [&](int kt, int kbuf) {
         const unsigned char* src = kcb + slab_of(kt);
-        const int g0 = opaque(k_goff0);
-        lds_dma16(src, g0, smem_base + kbuf * KV_BYTES + ld_lds);
-        lds_dma16(src, (g0 ^ 64) + 2048, smem_base + kbuf * KV_BYTES + ld_lds + 1024);
+        lds_dma16(src, k_goff0, smem_base + kbuf * KV_BYTES + ld_lds);
+        lds_dma16(src, xor_add_here(k_goff0, 64, 2048), smem_base + kbuf * KV_BYTES + ld_lds + 1024);
     };
     auto load_v = [&](int kt, int vbuf) {
         const unsigned char* src = vcb + slab_of(kt);
-        const int g0 = opaque(v_goff0);
-        lds_dma16(src, g0, smem_base + V_SM + vbuf * KV_BYTES + ld_lds);
-        lds_dma16(src, g0 + 1024, smem_base + V_SM + vbuf * KV_BYTES + ld_lds + 1024);
+        lds_dma16(src, v_goff0, smem_base + V_SM + vbuf * KV_BYTES + ld_lds);
+        lds_dma16(src, add_here<1024>(v_goff0), smem_base + V_SM + vbuf * KV_BYTES + ld_lds + 1024);
     };
     // after this wave's loads of V tile kt have landed: zero the rows (keys) it fetched that lie past
     // the request's tokens.  Only the request's last tile can have such rows.
@@ -469,10 +513,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     };
 
     f32x16 o_acc[4];
-#pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o_acc[nb][v] = 0.f;
 
     auto pv_tile = [&](int vbuf, const bf16x8 (&p)[2][2]) {  // O^T += V^T P^T
 #pragma unroll
@@ -494,16 +534,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 }
     };
 
-    float m_run = -INFINITY, l_run = 0.f;
+    // The weights are P = exp2(S c - mc) for a per-row reference exponent mc (in powers of two; c = log2(e) * scale).
+    // mc starts as the true maximum of the row's first tile and is NOT kept at the running maximum afterwards: any
+    // reference gives the same normalised result as long as nothing overflows, so the loop takes no row maxima at
+    // all.  It watches the row sums instead, which the matrix pipe delivers anyway: when a tile's sum passes
+    // 2^LAG_LOG2, mc is raised by a whole number of powers of two and O and l are scaled down by exactly that
+    // (see the end of iteration()).  mc never exceeds the row's true maximum, so the largest weight of a row is at
+    // least 1 and l cannot vanish.  A tile whose scores exceed everything before by more than about 2^90 would
+    // overflow before the sums can tell; l is then infinite at the end of the unit, and the unit is done again the
+    // slow, safe way (see `careful` below).
+    float mc_run, l_run;
     // log2(e) * scale, wave-uniform: kept in a scalar register
     const float c_log2 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(
         __builtin_bit_cast(int, b.softmax_scale * 1.44269504088896340736f)));
-    const float slack = RESCALE_LOG2 / c_log2;               // the lag allowed to the running maximum, in score units
 
     // P = exp2(S c - m c) rounded to bf16; l accumulates the rounded values (the same numbers the value
     // product uses), four at a time on the matrix pipe
     auto exp_tile = [&](const f32x16 (&s)[2], bf16x8 (&p)[2][2]) {
-        const float mc = m_run * c_log2;
+        const float mc = mc_run;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -544,6 +592,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         return pair_max(mx);
     };
 
+    mc_run = -INFINITY;
+    l_run = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o_acc[nb][v] = 0.f;
     if (n_tiles > 0) {
         // ---- prologue: the first tiles K(0), V(0), K(1), V(1), K(2) of this workgroup's range on their way
         //      to LDS (tile numbers in the comments below are relative to t_begin; ring slots follow them)
@@ -586,7 +640,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
 
         qk_tile(0, sc[0]);
         if (t_begin >= n_clear) mask_tile(t_begin, sc[0]);
-        m_run = row_max(sc[0]);                              // finite: every row sees a key of the first tile
+        mc_run = row_max(sc[0]) * c_log2;                    // finite: every row sees a key of the first tile
 
         // Iteration i (R = i % 4 fixed at compile time so that buffer offsets and register roles are
         // static).  K(i+1) is in K slot (R+1)%4, V(i) in V slot R, S(i) in sc[R & 1].  The tiles fetched
@@ -604,7 +658,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             const bool needs_mask = i + 1 >= n_clear;
             f32x16 (&s_cur)[2] = sc[R & 1];
             f32x16 (&s_nxt)[2] = sc[(R & 1) ^ 1];
-            const float mc = m_run * c_log2;
+            const float mc = mc_run;
             f32x4 psum = {0.f, 0.f, 0.f, 0.f};
             // Softmax work on S(i): 16 units; unit u = 8 kb + 4 s + j turns scores 8s + 2j, 8s + 2j + 1 of
             // key block kb into one register of the operand P[kb][s], with five instructions: F0 F1 (scale,
@@ -649,9 +703,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                     }
                 }
             };
-            auto softmax_slice = [&](auto slice_c) {         // slice 0 .. 23 of the iteration
+            auto softmax_slice = [&](auto slice_c) {         // slice 0 .. SOFTMAX_SLICES-1 of the iteration
                 constexpr int sl = decltype(slice_c)::value;
-                static_for<(sl * 90) / 24, ((sl + 1) * 90) / 24>(softmax_op);
+                static_for<(sl * 90) / SOFTMAX_SLICES, ((sl + 1) * 90) / SOFTMAX_SLICES>(softmax_op);
             };
             auto p_operand = [&](int kb, int sblk) -> bf16x8 {
                 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -660,26 +714,30 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             };
             fa[0] = fmaf(s_cur[0][0], c_log2, -mc);
             fb[0] = fmaf(s_cur[0][1], c_log2, -mc);
-            const int k_base = opaque(k_rd0), v_base = opaque(v_rd0);
-            auto read_k = [&](int k) -> bf16x8 {             // operand of QK slice k: step k/2, key block k%2
-                return *(const bf16x8*)(smem + ((R + 1) & 3) * KV_BYTES + (k & 1) * 32 * 256 + (k_base ^ ((k >> 1) << 5)));
+            int k_addr = k_rd0;                              // of the step last asked for
+            int v_addr[4] = {v_rd0, 0, 0, 0};                // of the four channel blocks: made at first use, then kept
+            auto read_k = [&](auto kc) -> bf16x8 {           // operand of QK slice k: step k/2, key block k%2
+                constexpr int k = decltype(kc)::value;
+                if constexpr ((k & 1) == 0) k_addr = xor_here<((k >> 1) << 5)>(k_rd0);
+                return *(const bf16x8*)(smem + ((R + 1) & 3) * KV_BYTES + (k & 1) * 32 * 256 + k_addr);
             };
-            auto read_v = [&](int k) -> bf16x8 {             // operand of PV slice k: kb = k/8, s = (k/4)%2, nb = k%4
+            auto read_v = [&](auto kc) -> bf16x8 {           // operand of PV slice k: kb = k/8, s = (k/4)%2, nb = k%4
+                constexpr int k = decltype(kc)::value;
                 typedef short s16x4 __attribute__((ext_vector_type(4)));
-                const unsigned char* src = smem + R * KV_BYTES + (32 * (k >> 3) + 16 * ((k >> 2) & 1)) * 256 + (v_base ^ ((k & 3) << 6));
+                if constexpr (k >= 1 && k < 4) v_addr[k] = xor_here<(k << 6)>(v_rd0);
+                const unsigned char* src = smem + R * KV_BYTES + (32 * (k >> 3) + 16 * ((k >> 2) & 1)) * 256 + v_addr[k & 3];
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
                 return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             };
 
             bf16x8 opnd[32 + PF_DIST];                       // operands in flight (short live ranges)
-#pragma unroll
-            for (int k = 0; k < PF_DIST; ++k) opnd[k] = read_k(k);
+            static_for<0, PF_DIST>([&](auto kc) { opnd[decltype(kc)::value] = read_k(kc); });
             __builtin_amdgcn_sched_barrier(0);
             static_for<0, 16>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                if constexpr (k + PF_DIST < 16) opnd[k + PF_DIST] = read_k(k + PF_DIST);
-                else opnd[k + PF_DIST] = read_v(k + PF_DIST - 16);
+                if constexpr (k + PF_DIST < 16) opnd[k + PF_DIST] = read_k(std::integral_constant<int, k + PF_DIST>{});
+                else opnd[k + PF_DIST] = read_v(std::integral_constant<int, k + PF_DIST - 16>{});
                 if constexpr (k < 2) {
                     f32x16 zero;
 #pragma unroll
@@ -703,31 +761,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             if (needs_mask) zero_v_tail(i + 1, (R + 1) & 3);  // such a tile lies beyond every wave's n_clear
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
-            float mx = 0.f;
             static_for<0, 16>([&](auto kc) {
                 constexpr int k = decltype(kc)::value;
-                if constexpr (k + PF_DIST < 16) opnd[16 + k + PF_DIST] = read_v(k + PF_DIST);
+                if constexpr (k + PF_DIST < 16) opnd[16 + k + PF_DIST] = read_v(std::integral_constant<int, k + PF_DIST>{});
                 o_acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[16 + k], p_operand(k >> 3, (k >> 2) & 1),
                                                                        o_acc[k & 3], 0, 0, 0);
                 if constexpr (k == 8) {
                     if (needs_mask) {
                         __builtin_amdgcn_sched_barrier(0);
-                        mask_tile(i + 1, s_nxt);             // before the maximum of S(i+1) is taken
+                        mask_tile(i + 1, s_nxt);             // before the next iteration turns S(i+1) into weights
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-                if constexpr (k < 8) {
-                    softmax_slice(std::integral_constant<int, 16 + k>{});
-                } else {
-                    // row maximum of S(i+1): 32 values, four per slice, written as max(max(a, b), running)
-                    // so that each pair costs one three-input maximum
-                    constexpr int kb = (k - 8) >> 2, v = 4 * ((k - 8) & 3);
-                    float m2;
-                    if constexpr (k == 8) m2 = fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]);
-                    else m2 = fmaxf(fmaxf(s_nxt[kb][v], s_nxt[kb][v + 1]), mx);
-                    mx = fmaxf(fmaxf(s_nxt[kb][v + 2], s_nxt[kb][v + 3]), m2);
-                }
-                if constexpr (k == 8) {
+                if constexpr (16 + k < SOFTMAX_SLICES) softmax_slice(std::integral_constant<int, 16 + k>{});
+                if constexpr (16 + k == SOFTMAX_SLICES) {
                     // row sums of P(i) on the matrix pipe, all eight back to back: switching between MFMA
                     // shapes costs the pipe about 16 cycles each time (measured), so they are not spread out
                     __builtin_amdgcn_sched_barrier(0);
@@ -740,27 +787,68 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
                 __builtin_amdgcn_sched_barrier(0);
             });
             l_run += psum[0];
-            // The running maximum only has to keep exp2 in range, so it is raised (and O, l rescaled)
-            // only when a row's new maximum exceeds it by more than 2^RESCALE_LOG2.  The common case costs
-            // one compare of this lane's half-row maximum against m_run + slack; only when some lane of the
-            // wave is over are the two halves of a row combined (both lanes of a row then decide alike).
-            if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {
-                mx = pair_max(mx);
-                const float m_new = (mx > m_run + slack) ? mx : m_run;
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+            // The reference exponent is raised only when a tile's row sum says that the weights have grown past
+            // 2^LAG_LOG2: one compare per tile in the common case.  The lane's sum covers its 32 keys of the tile,
+            // so sum / 32 <= largest weight <= sum: raising mc by floor(log2(sum)) - 5 powers of two, taken of the
+            // larger of the row's two lanes, leaves it at or below the row's true maximum, and scaling O and l
+            // by that power of two is exact.
+            if (__builtin_amdgcn_ballot_w64(psum[0] > LAG_LIMIT) != 0) {
+                const float big = pair_max(psum[0]);         // both lanes of a row decide alike
+                const int e = (int)(__float_as_uint(big) >> 23) - 127;          // big > 0: no sign bit
+                const int delta = big > LAG_LIMIT ? e - 5 : 0;                  // 15 .. 123
+                const float alpha = __uint_as_float((uint32_t)(127 - delta) << 23);
                 l_run *= alpha;
-                m_run = m_new;
+                mc_run += (float)delta;
 #pragma unroll
                 for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o_acc[nb][v] *= alpha;
             }
         };
+        // The same iteration the slow, safe way (second pass only): nothing interleaved, and before the
+        // exponentials of S(i) the row's reference exponent is raised to the true maximum seen so far, so that no
+        // weight exceeds 1.  Same ring slots, fetches, waits and barrier as above.
+        auto rescale_to_max = [&](const f32x16 (&s_cur)[2]) {
+            const float mxc = row_max(s_cur) * c_log2;       // finite from the first tile on
+            if (mxc > mc_run) {
+                const float alpha = __builtin_amdgcn_exp2f(mc_run - mxc);
+                l_run *= alpha;
+                mc_run = mxc;
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o_acc[nb][v] *= alpha;
+            }
+        };
+        auto careful_iteration = [&](int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
+            const int R = (i - t_begin) & 3;
+            if (i + 3 - pg_base >= 64) refill_pages(i + 2);
+            qk_tile((R + 1) & 3, s_nxt);
+            load_k(i + 3, (R + 3) & 3);
+            load_v(i + 2, (R + 2) & 3);
+            __builtin_amdgcn_s_waitcnt(0x0f74);              // vmcnt(4)
+            if (i + 1 >= n_clear) zero_v_tail(i + 1, (R + 1) & 3);
+            __syncthreads();
+            rescale_to_max(s_cur);
+            bf16x8 pc[2][2];
+            exp_tile(s_cur, pc);
+            pv_tile(R, pc);
+            if (i + 1 >= n_clear) mask_tile(i + 1, s_nxt);
+        };
         // four tiles per trip, straight-line (a tile's ring slot is its position in the body), then up to
         // three more; every wave runs n_tiles-1 iterations, one barrier each
         // (iteration() takes the absolute tile number; the ring slot is the position relative to t_begin)
         int i = t_begin;
         const int t_end = t_begin + n_tiles;
+        if constexpr (CAREFUL) {
+            for (; i + 2 < t_end; i += 2) {                  // S(i) lives in sc[(i - t_begin) & 1]
+                careful_iteration(i, sc[0], sc[1]);
+                careful_iteration(i + 1, sc[1], sc[0]);
+            }
+            if (i + 1 < t_end) careful_iteration(i, sc[0], sc[1]);
+            if ((n_tiles - 1) & 1) rescale_to_max(sc[1]);
+            else rescale_to_max(sc[0]);
+        } else {
         for (; i + 4 < t_end; i += 4) {
             if (i + 6 - pg_base >= 64) refill_pages(i + 2);  // tiles i+2 .. i+6 are fetched in this trip
             iteration(i, std::integral_constant<int, 0>{});
@@ -772,6 +860,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         if (i + 1 < t_end) iteration(i, std::integral_constant<int, 0>{});
         if (i + 2 < t_end) iteration(i + 1, std::integral_constant<int, 1>{});
         if (i + 3 < t_end) iteration(i + 2, std::integral_constant<int, 2>{});
+        }
         // ---- tail: tile n-1
         bf16x8 pf[2][2];
         switch ((n_tiles - 1) & 3) {
@@ -782,7 +871,45 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         }
         }                                                    // active
     }
+    // ---- every wave's fetches have landed and every wave is past its last read of the rings, which are free from
+    //      here on; then the vote: did any row of the workgroup overflow?
+    __builtin_amdgcn_s_waitcnt(0x0f70);                      // vmcnt(0)
+    __syncthreads();
+    if constexpr (!CAREFUL) {
+        const bool lane_bad = active && n_tiles > 0 && !(l_run < OVERFLOW_LIMIT);
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        __attribute__((address_space(3))) int* vote = (__attribute__((address_space(3))) int*)(smem + VOTE_OFFSET);
+        const int wave_bad = __builtin_amdgcn_ballot_w64(lane_bad) != 0 ? 1 : 0;      // taken by all lanes, stored by one
+        if (lane == 0) vote[wave] = wave_bad;
+        __syncthreads();
+        const i32x4 v0 = *(const __attribute__((address_space(3))) i32x4*)vote;
+        const i32x4 v1 = *(const __attribute__((address_space(3))) i32x4*)(vote + 4);
+        const int any = v0[0] | v0[1] | v0[2] | v0[3] | v1[0] | v1[1] | v1[2] | v1[3];
+        if (__builtin_amdgcn_readfirstlane(any) != 0) {
+            __syncthreads();                                 // all have read the votes before the second pass refills the rings
+            attend_unit_carefully<CAUSAL>((unsigned long long)(uintptr_t)__builtin_amdgcn_kernarg_segment_ptr(), xcd, in_xcd,
+                                          (lds_bytes)smem);
+            // the wave ends here: said in so many words, because otherwise the accumulators count as live across
+            // the call and are kept in private memory from here to the epilogue on the fast path too
+            __builtin_amdgcn_endpgm();
+        }
+    }
 
+#ifdef EMM_TIMELINE
+    // one record per workgroup at the head of the workspace (the pieces follow): start, end of the tile loop (100 MHz ticks),
+    // shader cycles in between, key tiles done, where it ran (HW_ID: compute unit, shader engine; XCC_ID), which unit
+    if (threadIdx.x == 0 && blockIdx.x < TIMELINE_RECORDS) {
+        long long* rec = (long long*)a.workspace + 8 * (long long)blockIdx.x;
+        rec[0] = tl_t0;
+        rec[1] = __builtin_amdgcn_s_memrealtime();
+        rec[2] = __builtin_readcyclecounter() - tl_c0;
+        rec[3] = n_tiles;
+        rec[4] = __builtin_amdgcn_s_getreg(4 | (31 << 11));            // HW_REG_HW_ID, all 32 bits
+        rec[5] = __builtin_amdgcn_s_getreg(20 | (3 << 11));            // HW_REG_XCC_ID, bits 3:0
+        rec[6] = ((long long)pair << 32) | (unsigned)(tile * 64 + plan.part);
+        rec[7] = cut;
+    }
+#endif
     // ---- epilogue.  The row bookkeeping is recomputed from an opaque copy of the thread index so that
     //      none of it has to stay in registers across the main loop.
     {
@@ -798,16 +925,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
             for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) ws[(16 * nb + v) * NTHREADS] = o_acc[nb][v];
-            ws[64 * NTHREADS] = m_run;
+            ws[64 * NTHREADS] = mc_run;
             ws[65 * NTHREADS] = l_part;
             return;
         }
         // The normalised rows go to global memory through LDS, so that a store instruction writes four whole
         // rows of 256 bytes (16 lanes x 16 bytes each): written straight from the accumulator layout, every
         // lane of an instruction would touch a different row, which costs about 2 us per workgroup.  The rings
-        // are free once every wave's fetches have landed and every wave is past its last read.
-        __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0)
-        __syncthreads();
+        // are free by now (see above).
         if (!active) return;
         const int e_wave = t2 >> 6, e_lane = t2 & 63;
         const int e_l32 = e_lane & 31, e_h32 = e_lane >> 5;
@@ -828,7 +953,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
         if (a.lse != nullptr && e_h32 == 0 && e_row < n_rows) {
             const int e_tok = e_row / G;
             a.lse[((long long)first_row + e_tok) * b.num_q_heads + kvh * G + (e_row - e_tok * G)] =
-                (l_tot > 0.f) ? m_run * b.softmax_scale + logf(l_tot) : -INFINITY;
+                (l_tot > 0.f) ? mc_run * 0.69314718055994530942f + logf(l_tot) : -INFINITY;
         }
         // the wave's own LDS writes are visible to its own reads once they have completed
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -850,16 +975,53 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(AttnArgs a,
     }
 }
 
+// The second, safe pass over a work item whose weights overflowed.  A function of its own, not inlined: its
+// registers are allocated apart from the fast path's, which has none to spare, and nothing of the caller has to
+// survive the call.  It reads the kernel's arguments from the kernel argument segment, whose address the kernel
+// hands over (asked for in here, in a function that is not a kernel, that address comes out as null), rather than
+// through a copy in private memory, and works the item's plan out again.
+template <bool CAUSAL>
+__device__ __attribute__((noinline)) void attend_unit_carefully(unsigned long long kernargs_v, int xcd_v, int in_xcd_v, lds_bytes lds_v)
+{
+    // arguments arrive in vector registers; everything here is the same in all lanes, and the tile loads want their
+    // base addresses in scalar registers
+    const int xcd = __builtin_amdgcn_readfirstlane(xcd_v), in_xcd = __builtin_amdgcn_readfirstlane(in_xcd_v);
+    const lds_bytes lds = (lds_bytes)(uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)lds_v);
+    const unsigned long long kernargs =
+        ((unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(kernargs_v >> 32)) << 32) |
+        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)kernargs_v);
+    const KernArgs* __restrict__ ka = (const KernArgs*)(const __attribute__((address_space(4))) KernArgs*)kernargs;
+    const AttnArgs& a = ka->a;
+    const LaunchShape& L = ka->L;
+    const UnitPlan plan = plan_unit(a.b, a.b.num_q_heads / a.b.num_kv_heads, L, xcd, in_xcd);
+    if (plan.pair < 0) return;
+    attend_unit<CAUSAL, true>(a, L, xcd, in_xcd, plan, (unsigned char*)lds);
+}
+
+template <bool CAUSAL>
+__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_d128_kernel(KernArgs ka)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * NBUF * KV_BYTES];   // K ring, then V ring
+    const AttnArgs& a = ka.a;
+    const LaunchShape& L = ka.L;
+    const BatchView& b = a.b;
+    // Workgroups are dealt to the 8 XCDs round-robin by the dispatcher; plan_unit() says which unit, and which
+    // part of its key range, this one does.
+    const int xcd = blockIdx.x % NUM_XCD, in_xcd = blockIdx.x / NUM_XCD;
+    const UnitPlan plan = plan_unit(b, b.num_q_heads / b.num_kv_heads, L, xcd, in_xcd);
+    if (plan.pair < 0) return;
+    attend_unit<CAUSAL, false>(a, L, xcd, in_xcd, plan, smem);
+}
+
 // One workgroup's share of the merge of a unit planned for PARTS pieces and cut into `cut` of them: REGS = 64 / SHARES
 // consecutive ones of each thread's 64 accumulator registers (32 pieces: 32 shares of 2 registers, so that what is
 // in flight fits the register file).  Every load is issued whatever `cut` is (pieces past the last repeat it,
 // with weight 0), all of them before the first use, so that one memory latency covers them.
 template <int PARTS, int SHARES = PARTS>
-__device__ inline void merge_share(const float* __restrict__ ws0, unsigned tid, int cut, int sub, float scale,
+__device__ inline void merge_share(const float* __restrict__ ws0, unsigned tid, int cut, int sub,
                                    __bf16* __restrict__ op, int h32, float* __restrict__ lse)
 {
     // ws0 is the same for the whole workgroup and tid a 32-bit offset: loads with a scalar base, no address registers
-    const float c_log2 = scale * 1.44269504088896340736f;
     constexpr int REGS = 64 / SHARES;
     float m_part[PARTS], l_part[PARTS], val[PARTS][REGS];
 #pragma unroll
@@ -879,7 +1041,7 @@ __device__ inline void merge_share(const float* __restrict__ ws0, unsigned tid, 
     for (int i = 0; i < REGS; ++i) acc[i] = 0.f;
 #pragma unroll
     for (int j = 0; j < PARTS; ++j) {
-        const float w = j < cut ? __builtin_amdgcn_exp2f((m_part[j] - m_all) * c_log2) : 0.f;
+        const float w = j < cut ? __builtin_amdgcn_exp2f(m_part[j] - m_all) : 0.f;
         l_tot += w * l_part[j];
 #pragma unroll
         for (int i = 0; i < REGS; ++i) acc[i] += w * val[j][i];
@@ -902,7 +1064,7 @@ __device__ inline void merge_share(const float* __restrict__ ws0, unsigned tid, 
             *(bf16x4*)(op + 32 * (g >> 2) + 8 * (g & 3) + 4 * h32) = o;
         }
     }
-    if (lse != nullptr) *lse = (l_tot > 0.f) ? m_all * scale + logf(l_tot) : -INFINITY;
+    if (lse != nullptr) *lse = (l_tot > 0.f) ? m_all * 0.69314718055994530942f + logf(l_tot) : -INFINITY;
 }
 
 // Merges the pieces of the cut units, thread for thread the layout of the main kernel's epilogue.  An XCD
@@ -942,15 +1104,15 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
     float* lse = (a.lse != nullptr && h32 == 0 && plan.part == 0) ? a.lse + q_row * b.num_q_heads + hq : nullptr;
     if (plan.uneven > 0) {
-        merge_share<2, 1>(ws0, tid, cut, 0, b.softmax_scale, op, h32, lse);
+        merge_share<2, 1>(ws0, tid, cut, 0, op, h32, lse);
         return;
     }
     switch (plan.parts) {
-        case 2: merge_share<2>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        case 4: merge_share<4>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        case 8: merge_share<8>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        case 16: merge_share<16>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
-        default: merge_share<32>(ws0, tid, cut, plan.part, b.softmax_scale, op, h32, lse); break;
+        case 2: merge_share<2>(ws0, tid, cut, plan.part, op, h32, lse); break;
+        case 4: merge_share<4>(ws0, tid, cut, plan.part, op, h32, lse); break;
+        case 8: merge_share<8>(ws0, tid, cut, plan.part, op, h32, lse); break;
+        case 16: merge_share<16>(ws0, tid, cut, plan.part, op, h32, lse); break;
+        default: merge_share<32>(ws0, tid, cut, plan.part, op, h32, lse); break;
     }
 }
 
@@ -958,7 +1120,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
 
 size_t attn_bf16_d128_workspace_bytes()
 {
-    return (size_t)NUM_XCD * PIECES_PER_XCD * PART_FLOATS * sizeof(float);
+    return (size_t)NUM_XCD * PIECES_PER_XCD * PART_FLOATS * sizeof(float) + TIMELINE_BYTES;
 }
 
 // The launch shape of a batch, from what the host knows: the scalar fields and whether there is a workspace.
@@ -1051,9 +1213,9 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     const long long grid = NUM_XCD * per_xcd;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
     if (a.causal)
-        hipLaunchKernelGGL(attn_bf16_d128_kernel<true>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, L);
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<true>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, KernArgs{a, L});
     else
-        hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, L);
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, KernArgs{a, L});
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || !L.split) return err;
     // no context of this batch is long enough to be cut along the keys (two pieces of the usual minimum, or four

@@ -635,6 +635,53 @@ def test_kv_page_checksum_of_the_largest_page():
     assert k2.cpu().numpy().tobytes() == k_ref.tobytes() and v2.cpu().numpy().tobytes() == v_ref.tobytes()
 
 
+def _plant_key(wl, r, pos, value):
+    """Every channel of key `pos` of request r (all KV heads) becomes `value`: in the pool if the key is cached,
+    else in k_new."""
+    bits = W.to_bf16_bits(np.full((wl.num_kv_heads, wl.head_dim), value, np.float32))
+    P = int(wl.prefix_lens[r])
+    if wl.kind == "cross" or pos < P:
+        wl.k_cache[wl.page_table[r, pos // wl.page_size], :, pos % wl.page_size, :] = bits
+    else:
+        wl.k_new[int(wl.cu_new_lens[r]) + pos - P] = bits
+
+
+STEEP_CASES = [
+    # name, kind, H, Hkv, prefix lens, new lens, planted keys (request, position, value of every channel)
+    # With every query channel 4.0, a key of all 0.6 scores 39 powers of two and a key of all 4.0 scores 261 powers of two
+    # above the usual ones: the first makes the kernel raise its reference exponent on the way (row sums past 2^20), the
+    # second overflows single precision between two tiles, which the kernel must notice and do the unit again with true
+    # running maxima.
+    ("steep_mid", "causal", 28, 4, [100, 0], [300, 500], [(0, 250, 0.6), (1, 130, 0.6), (1, 390, 0.6)]),
+    ("steep_big", "causal", 28, 4, [100, 0], [300, 500], [(0, 250, 4.0), (1, 130, 0.6), (1, 390, 4.0)]),
+    ("steep_big_prefix", "causal", 8, 2, [4000, 700], [200, 40], [(0, 3000, 4.0), (0, 600, 0.6), (1, 699, 4.0)]),
+    ("steep_cut", "causal", 28, 4, [5000], [64], [(0, 3000, 4.0), (0, 900, 0.6)]),         # pieces of cut units, merged
+    ("steep_cut_mid", "causal", 28, 4, [5000], [64], [(0, 3000, 0.6), (0, 4500, 0.6)]),
+    ("steep_cross", "cross", 32, 8, [6404, 1601], [100, 300], [(0, 5000, 4.0), (1, 1600, 4.0), (1, 70, 0.6)]),
+    ("steep_first_tile", "causal", 28, 4, [0], [400], [(0, 3, 4.0)]),                       # the dominant key comes first
+]
+
+
+@pytest.mark.parametrize("name,kind,H,Hkv,prefix,new,planted", STEEP_CASES)
+def test_scores_that_jump_between_tiles(name, kind, H, Hkv, prefix, new, planted):
+    """The prefill kernel takes no row maxima on the way (it watches the row sums); scores that rise steeply from one
+    key tile to a later one must still come out right: by raising the reference exponent, or, past the range of
+    single precision, by the second, careful pass."""
+    print("case", name, flush=True)
+    wl = W.build_workload(name, kind, "bf16", 1700 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=prefix, new_lens=new)
+    wl.q[...] = W.to_bf16_bits(np.full(wl.q.shape, 4.0, np.float32))
+    for r, pos, value in planted:
+        _plant_key(wl, r, pos, value)
+    dw = _gpu_run(wl)
+    print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
+    first = B.DeviceWorkload.to_numpy_bits(dw.out).tobytes()
+    dw.out.zero_()
+    dw.attention()                                      # same bits on a second run (stale workspace, same decisions)
+    torch.cuda.synchronize()
+    assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == first
+
+
 def test_f32_head_dim_128_and_cross():
     print("case f32 d=128 causal + cross", flush=True)
     wl = W.build_workload("f32_128", "causal", "f32", 700, num_q_heads=6, num_kv_heads=2, head_dim=128,
