@@ -18,7 +18,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-BF16_MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz (published dense bf16 figure, 2.5 PF)
+BF16_MFMA_PEAK_TFLOPS = 2500.0     # published dense bf16 MFMA figure of MI355X (256 CUs x 4096 flop/clk x 2.4 GHz = 2516.6)
 HBM_PEAK_GBS = 8000.0
 
 
@@ -75,23 +75,99 @@ def cpu_baseline(wl, target_tokens):
             "new_tokens_per_s": len(tokens) / dt}
 
 
-def read_decode_traffic(name):
-    """HBM bytes per launch of the decode main kernel measured with rocprofv3 --pmc (see profiles/), if recorded."""
-    try:
-        with open(os.path.join(ROOT, "profiles", "attn_bf16_decode_hbm_traffic.json")) as f:
-            return json.load(f).get(name, {}).get("traffic_bytes_per_launch")
-    except (OSError, ValueError):
-        return None
+def source_digest(*names):
+    """sha256 over the named kernel sources: a recorded counter figure is only shown next to measurements of the
+    kernels it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2507_10069_amd", "csrc", n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
-def read_traffic():
-    """HBM bytes per attention launch measured with rocprofv3 --pmc (see profiles/), if recorded."""
-    path = os.path.join(ROOT, "profiles", "attn_bf16_cfg3_hbm_traffic.json")
+def recorded_traffic(path, key, sources):
+    """HBM bytes per launch of the dominant kernel from a rocprofv3 --pmc run recorded under profiles/ (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size).  It is a figure from an
+    EARLIER run of the same workload, not of this one: returned with its provenance, and dropped (None) when the
+    kernel sources have changed since it was recorded.  Returns (bytes or None, provenance dict or None)."""
     try:
-        with open(path) as f:
-            return json.load(f).get("traffic_bytes_per_launch")
+        with open(os.path.join(ROOT, "profiles", path)) as f:
+            rec = json.load(f)
     except (OSError, ValueError):
-        return None
+        return None, None
+    rec = rec.get(key, rec) if key else rec
+    if not isinstance(rec, dict) or "traffic_bytes_per_launch" not in rec:
+        return None, None
+    prov = {"file": "profiles/" + path, "recorded": rec.get("recorded"), "fetch_scale": rec.get("fetch_scale"),
+            "write_scale": rec.get("write_scale"), "kernel_sources_sha256": rec.get("kernel_sources_sha256"),
+            "measured_in_this_run": False}
+    if rec.get("kernel_sources_sha256") != source_digest(*sources):
+        prov["stale"] = "kernel sources differ from the recorded ones: figure withheld"
+        return None, prov
+    return rec["traffic_bytes_per_launch"], prov
+
+
+PREFILL_SOURCES = ("attn_bf16.hip", "attn_bf16_common.h", "emm_internal.h")
+DECODE_SOURCES = ("attn_bf16_decode.hip", "attn_bf16_common.h", "emm_internal.h")
+
+
+def bench_timeline(workload):
+    """One launch of the prefill kernel built with -DEMM_TIMELINE (python -m paper_2507_10069_amd.build --timeline):
+    every workgroup leaves start / end time stamps (100 MHz), its shader cycle count, its key tiles and where it ran
+    (XCC_ID, HW_ID); printed as a summary per round of workgroups and per XCD."""
+    import numpy as np
+    import torch
+    from paper_2507_10069_amd import binding as B
+    from paper_2507_10069_amd import workloads as W
+    from paper_2507_10069_amd import build as hip_build
+    if not os.path.exists(hip_build.TIMELINE_LIB):
+        sys.exit("bench.py --timeline: build the instrumented library first: python -m paper_2507_10069_amd.build --timeline")
+    B.LIB_PATH = hip_build.TIMELINE_LIB
+    n_rec = 16384
+    wl = W.config(workload)
+    dw = B.DeviceWorkload(wl)
+    if dw.workspace is None or dw.workspace.numel() < n_rec * 64:
+        sys.exit("bench.py --timeline: the instrumented library was not loaded")
+    dw.scatter()
+    for _ in range(20):
+        dw.attention()
+    torch.cuda.synchronize()
+    dw.workspace[:n_rec * 64].zero_()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):                                  # the records of the last of three launches back to back
+        e0.record()
+        dw.attention()
+        e1.record()
+    torch.cuda.synchronize()
+    rec = dw.workspace[:n_rec * 64].view(torch.int64).cpu().numpy().reshape(n_rec, 8)
+    idx = np.nonzero(rec[:, 1] > 0)[0]
+    r = rec[idx]
+    t0 = r[:, 0].min()
+    start, end = (r[:, 0] - t0) / 100.0, (r[:, 1] - t0) / 100.0            # microseconds
+    dur, cyc, tiles = end - start, r[:, 2].astype(np.float64), r[:, 3].astype(np.float64)
+    xcc, cu, sh, se = r[:, 5] & 15, (r[:, 4] >> 8) & 15, (r[:, 4] >> 12) & 1, (r[:, 4] >> 13) & 7
+    mfma = tiles * 64.0                                 # per SIMD: two waves x 32 MFMAs per key tile
+    print("workload %s: kernel %.1f us by HIP events; %d workgroups with work, first start to last end %.1f us"
+          % (wl.name, e0.elapsed_time(e1) * 1e3, len(r), end.max()))
+    print("XCC_ID equals workgroup index mod 8 for %d of %d workgroups" % (int((xcc == idx % 8).sum()), len(r)))
+    first_end = end.min()
+    for name, sel in (("first round (started before any workgroup ended)", start < first_end), ("later rounds", start >= first_end)):
+        if sel.sum() == 0:
+            continue
+        busy = len(set(zip(xcc[sel].tolist(), se[sel].tolist(), sh[sel].tolist(), cu[sel].tolist())))
+        print("%s: %d workgroups on %d compute units; start %.1f .. %.1f us, end %.1f .. %.1f us; mean duration %.1f us; "
+              "%.3f us per key tile; shader clock %.0f MHz; %.1f cycles per MFMA (32 = matrix pipe always busy)"
+              % (name, int(sel.sum()), busy, start[sel].min(), start[sel].max(), end[sel].min(), end[sel].max(), dur[sel].mean(),
+                 (dur[sel] / tiles[sel]).mean(), (cyc[sel] / dur[sel]).mean(), (cyc[sel] / mfma[sel]).mean()))
+    for x in range(8):
+        sel = xcc == x
+        if sel.sum():
+            print("  XCD %d: %3d workgroups, first start %.1f us, last end %.1f us" % (x, int(sel.sum()), start[sel].min(), end[sel].max()))
+    print("XCD finish spread: %.1f us (%.1f %% of the span)" % (max(end[xcc == x].max() for x in set(xcc.tolist())) -
+          min(end[xcc == x].max() for x in set(xcc.tolist())), 100.0 * (max(end[xcc == x].max() for x in set(xcc.tolist())) -
+          min(end[xcc == x].max() for x in set(xcc.tolist()))) / end.max()))
 
 
 def bench_prefix_cache(with_model: bool):
@@ -252,6 +328,9 @@ def main():
                          "suffix_b1_16k_n36, suffix_b8_16k_n36, suffix_b8_16k_n4 or suffix_b32_4k_n36")
     ap.add_argument("--kv-migrate", action="store_true",
                     help="time the KV page migration primitive (pack and unpack with checksums) instead")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-workgroup timeline of one prefill launch of --workload (needs the build made by "
+                         "python -m paper_2507_10069_amd.build --timeline)")
     ap.add_argument("--prefix-cache", action="store_true",
                     help="time the host-side prefix cache (no GPU work) on a synthetic request stream")
     args = ap.parse_args()
@@ -267,8 +346,10 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
-    B.load()                                            # fails loudly if libemm.so has not been built
     torch.cuda.set_device(0)
+    if args.timeline:
+        return bench_timeline(args.workload)
+    B.load()                                            # fails loudly if libemm.so has not been built
 
     if args.copy_calibration:
         src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda").fill_(1)
@@ -369,6 +450,7 @@ def main():
         torch.cuda.synchronize()
         fused["planned_graph_replay"] = e0.elapsed_time(e1) / args.steps
         log("  the planned step replayed from a HIP graph: %.4f ms" % fused["planned_graph_replay"])
+        decode_traffic, decode_traffic_source = recorded_traffic("attn_bf16_decode_hbm_traffic.json", wl.name, DECODE_SOURCES)
         print(json.dumps({
             "metric": "decode_attention_kv_read_gbs", "value": distinct / (ms * 1e-3) / 1e9, "unit": "GB/s",
             "kv_consumed_gbs": wl.kv_read_bytes() / (ms * 1e-3) / 1e9,     # shared pages counted once per request
@@ -379,7 +461,7 @@ def main():
             "new_tokens_per_s": wl.total_new_tokens / (ms * 1e-3), "attention_ms": attn_ms, "scatter_ms": scat_ms,
             "kv_distinct_bytes_per_step": distinct,
             "roofline": {"bound": "hbm", "achieved": distinct_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": distinct_gbs / HBM_PEAK_GBS, "traffic": read_decode_traffic(wl.name),
+                         "frac": distinct_gbs / HBM_PEAK_GBS, "traffic": decode_traffic, "traffic_source": decode_traffic_source,
                          "kernel": "attn_bf16_decode_kernel + attn_bf16_decode_merge_kernel"},
             "shared_prefix": shared, "fused_step_ms": fused,
         }), flush=True)
@@ -395,6 +477,7 @@ def main():
     log("workload %s: %.4f ms/step (attention %.4f ms, scatter %.4f ms), %.1f TFLOP/s whole step, "
         "%.1f TFLOP/s attention kernel" % (wl.name, ms, attn_ms, scat_ms, tflops, attn_tflops))
 
+    traffic, traffic_source = recorded_traffic("attn_bf16_cfg%d_hbm_traffic.json" % args.workload, None, PREFILL_SOURCES)
     result = {
         "metric": "prefill_attention_tflops", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
@@ -410,7 +493,7 @@ def main():
         "attention_ms": attn_ms, "scatter_ms": scat_ms,
         "scatter_gbs": (wl.scatter_bytes() / (scat_ms * 1e-3) / 1e9) if scat_ms > 0 else None,
         "roofline": {"bound": "mfma", "achieved": attn_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": attn_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": read_traffic(),
+                     "frac": attn_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "attn_bf16_d128_kernel"},
     }
     if args.others:

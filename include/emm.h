@@ -98,13 +98,19 @@ emm_status emm_kv_scatter(const emm_batch *batch, const void *k_new, const void 
                           void *k_cache, void *v_cache, void *hip_stream);
 
 /* Bytes of device workspace emm_prefill_attn / emm_cross_attn / emm_decode_attn need for this batch: 0 for
- * EMM_F32; for EMM_BF16 about 69 MB, or, for a decode batch (at most one new token per request and at most
- * 16 query heads per KV head), 8320 bytes per (request, KV head, piece), a piece being 128 to 1920 keys of the
- * longest context the page table can hold.  The bf16 kernels cut work along the key axis (prefill: the work
- * units left over after an XCD's full rounds of 32, in up to 32 pieces; decode: every context), park the pieces' accumulators
- * there and merge them with a second kernel on the same stream; the contents need no initialisation and mean
- * nothing afterwards.  Calls on different streams must not share a workspace.  Host-only; reads only the
- * scalar fields. */
+ * EMM_F32.  For EMM_BF16 the kernels cut work along the key axis, park the pieces' accumulators in the workspace
+ * and merge them with a second kernel on the same stream:
+ *   prefill / cross-attention: the work units an XCD has left over after its full rounds of 32 are cut in up to 32
+ *     pieces; a piece record is 135168 bytes, and the size is 8 XCDs x the most records an XCD can need: exactly that
+ *     of the plan when all requests have the same number of new tokens (0 when that plan cuts nothing, as for 2 x
+ *     2048 new tokens on 28 / 4 heads), else a bound from the scalar fields (32 or 64 records per XCD: 34.6 or 69.2
+ *     MB), and 0 when no context the page table can hold is long enough to be cut (under 1536 tokens);
+ *     emm_prefill_plan_host shows the plan;
+ *   decode batch (at most one new token per request and at most 16 query heads per KV head): every context is
+ *     cut; 8320 bytes per (request, KV head, piece), a piece being 128 to 1920 keys of the longest context the
+ *     page table can hold.
+ * The contents need no initialisation and mean nothing afterwards.  Calls on different streams must not share a
+ * workspace.  Host-only; reads only the scalar fields. */
 emm_status emm_prefill_attn_workspace_size(const emm_batch *batch, size_t *bytes);
 
 /*

@@ -13,6 +13,7 @@ a cache and serves as one of the oracle's pins.  The functions here only marshal
 from __future__ import annotations
 
 import ctypes
+import os
 from typing import Optional, Sequence
 
 import numpy as np
@@ -29,7 +30,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     global _lib
     if path is None and _lib is not None:
         return _lib
-    lib = ctypes.CDLL(path or _build.build())
+    # EMM_ORACLE_LIB names another build of the same source (the sanitized one of tests/test_sanitized_host.py)
+    lib = ctypes.CDLL(path or os.environ.get("EMM_ORACLE_LIB") or _build.build())
     i32p, vp, i64p, f64p = (ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p,
                             ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double))
     ci, cd, c64 = ctypes.c_int, ctypes.c_double, ctypes.c_int64

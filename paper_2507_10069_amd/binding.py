@@ -14,7 +14,8 @@ from typing import Optional
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libemm.so")
+# EMM_LIB_PATH names another build of the same library (the host-sanitized one that tests/test_sanitized_host.py runs)
+LIB_PATH = os.environ.get("EMM_LIB_PATH") or os.path.join(HERE, "libemm.so")
 
 EMM_OK, EMM_ERR_NULL, EMM_ERR_INVALID_ARG, EMM_ERR_UNSUPPORTED, EMM_ERR_WORKSPACE, EMM_ERR_LAUNCH = range(6)
 EMM_F32, EMM_BF16 = 0, 1

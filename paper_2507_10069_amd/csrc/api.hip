@@ -181,7 +181,7 @@ emm_status emm_prefill_attn_workspace_size(const emm_batch* b, size_t* bytes)
     if (b->dtype == EMM_BF16) {
         const emm::BatchView v = view_of(b);
         *bytes = emm::attn_bf16_decode_applies(v) ? emm::attn_bf16_decode_workspace_bytes(v)
-                                                  : emm::attn_bf16_d128_workspace_bytes();
+                                                  : emm::attn_bf16_d128_workspace_bytes(v);
     }
     return EMM_OK;
 }

@@ -153,6 +153,7 @@ struct LaunchShape {
     int split;              // 1: tail units may be cut (workspace present)
     int fan;                // sub-pairs per (request, KV head) pair: 1, 2, 4 or 8
     int uneven;             // 1: 17 .. 30 units in an XCD's last round are cut unevenly (see uneven_of)
+    int ws_pieces;          // piece records per XCD that the workspace holds
 };
 
 struct UnitPlan {
@@ -313,10 +314,11 @@ __device__ inline UnitPlan plan_unit(const BatchView& b, int G, const LaunchShap
     return u;
 }
 
-// workspace of pieces: [xcd][tail slot x planned pieces per unit + piece][66][512] floats
-__device__ inline float* part_base(void* workspace, int xcd, int slot, int parts, int part)
+// Workspace: a timeline build's records, then the piece records, [xcd][tail slot x planned pieces per unit + piece]
+// [66][512] floats, ws_pieces of them per XCD.
+__device__ inline float* part_base(void* workspace, int ws_pieces, int xcd, int slot, int parts, int part)
 {
-    return (float*)((unsigned char*)workspace + TIMELINE_BYTES) + (size_t)(xcd * PIECES_PER_XCD + slot * parts + part) * PART_FLOATS;
+    return (float*)((unsigned char*)workspace + TIMELINE_BYTES) + (size_t)(xcd * ws_pieces + slot * parts + part) * PART_FLOATS;
 }
 
 struct KernArgs {
@@ -919,7 +921,7 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
             // a piece of a cut unit: unnormalised accumulator, running maximum and row sum go to the
             // workspace, one coalesced row of 512 floats per register; attn_bf16_merge_kernel finishes
             if (!active) return;                             // a wave without rows has nothing to hand over
-            float* __restrict__ ws = part_base(a.workspace, xcd, plan.slot, plan.parts, plan.part) + t2;
+            float* __restrict__ ws = part_base(a.workspace, L.ws_pieces, xcd, plan.slot, plan.parts, plan.part) + t2;
             const float l_part = pair_sum(l_run);
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
@@ -1100,7 +1102,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
     const int tok = row / G;
     const int hq = kvh * G + (row - tok * G);
     const long long q_row = (long long)safe_first_row(b, r, N) + tok;
-    const float* __restrict__ ws0 = part_base(a.workspace, xcd, plan.slot, plan.parts, 0);
+    const float* __restrict__ ws0 = part_base(a.workspace, L.ws_pieces, xcd, plan.slot, plan.parts, 0);
     __bf16* __restrict__ op = (__bf16*)a.out + (q_row * b.num_q_heads + hq) * D;
     float* lse = (a.lse != nullptr && h32 == 0 && plan.part == 0) ? a.lse + q_row * b.num_q_heads + hq : nullptr;
     if (plan.uneven > 0) {
@@ -1118,9 +1120,11 @@ __global__ __launch_bounds__(NTHREADS) void attn_bf16_merge_kernel(AttnArgs a, L
 
 }  // namespace
 
-size_t attn_bf16_d128_workspace_bytes()
+static bool long_enough_to_cut(const BatchView& b)
 {
-    return (size_t)NUM_XCD * PIECES_PER_XCD * PART_FLOATS * sizeof(float) + TIMELINE_BYTES;
+    constexpr long long MIN_CUT_TILES = 2 * MIN_TILES_PER_PART < MIN_UNIT_TILES_UNDERFILLED ? 2 * MIN_TILES_PER_PART : MIN_UNIT_TILES_UNDERFILLED;
+    static_assert(4 * MIN_TILES_PER_PART_UNDERFILLED <= MIN_UNIT_TILES_UNDERFILLED, "short pieces come four or more at a time");
+    return ((long long)b.max_pages * b.page_size + BC - 1) / BC >= MIN_CUT_TILES;
 }
 
 // The launch shape of a batch, from what the host knows: the scalar fields and whether there is a workspace.
@@ -1142,10 +1146,11 @@ static void launch_shape(const BatchView& b, bool has_workspace, LaunchShape& L,
     L.fan = fan;
     L.split = (has_workspace && pairs_per_xcd <= SPLIT_MAX_PAIRS_PER_XCD) ? 1 : 0;
     L.uneven = 1;
-    if (L.split && (long long)b.num_reqs * b.max_new_len == b.total_new_tokens) {
+    const bool uniform = L.split && (long long)b.num_reqs * b.max_new_len == b.total_new_tokens;
+    long long units[NUM_XCD] = {};
+    if (uniform) {
         // every request has max_new_len new tokens, so the host knows each XCD's unit count and can tell
         // whether any tail unit would be cut at all; if none, the extra workgroups and the merge launch go
-        long long units[NUM_XCD];
         bool alike = true;
         for (int x = 0; x < NUM_XCD; ++x) {
             units[x] = 0;
@@ -1162,6 +1167,24 @@ static void launch_shape(const BatchView& b, bool has_workspace, LaunchShape& L,
             any = any || split_factor((int)(units[x] % CU_PER_XCD), (int)(units[x] / CU_PER_XCD), L.uneven) > 1;
         if (!any) L.split = 0;
     }
+    L.ws_pieces = 0;
+    if (L.split && long_enough_to_cut(b)) {
+        // Piece records of an XCD: tail slot x planned pieces + piece.  r units left over are planned for p pieces
+        // with r p <= 32, or for 2 (an uneven cut of 17 .. 30 units): at most 60, which takes 17 units on the XCD.
+        // (A context too short to be cut along the keys -- two pieces of the usual minimum, or four short ones on an
+        // under-filled XCD -- leaves no records: left-over units can then only be halved along their rows.)
+        long long most = 0;
+        if (uniform) {
+            for (int x = 0; x < NUM_XCD; ++x) {
+                const int rem = (int)(units[x] % CU_PER_XCD), full = (int)(units[x] / CU_PER_XCD);
+                const int p = rows_only_of(rem, full) ? 1 : split_factor(rem, full, L.uneven);
+                most = std::max<long long>(most, p > 1 ? (long long)rem * p : 0);
+            }
+        } else {
+            most = pairs_per_xcd * n_row_tiles > CU_PER_XCD / 2 ? PIECES_PER_XCD : CU_PER_XCD;
+        }
+        L.ws_pieces = (int)most;
+    }
     slots = pairs_per_xcd * n_row_tiles;                                 // one per row tile of the longest request, per pair
     if (L.split && fan == 1) {
         // With cutting, workgroup j of an XCD takes the XCD's unit j, so the grid only has to cover the units there
@@ -1173,6 +1196,15 @@ static void launch_shape(const BatchView& b, bool has_workspace, LaunchShape& L,
                                 ((long long)b.total_new_tokens * G / BR + b.num_reqs);
         slots = slots < bound ? slots : bound;
     }
+}
+
+// bytes behind AttnArgs::workspace that launch_attn_bf16_d128 wants for this batch
+size_t attn_bf16_d128_workspace_bytes(const BatchView& b)
+{
+    LaunchShape L;
+    long long slots = 0;
+    launch_shape(b, true, L, slots);
+    return TIMELINE_BYTES + (size_t)NUM_XCD * L.ws_pieces * PART_FLOATS * sizeof(float);
 }
 
 // What the planner makes of a batch whose new-token counts are given as a host array: the launch shape and, per
@@ -1208,7 +1240,8 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     if (b.total_new_tokens == 0 || b.num_reqs == 0) return hipSuccess;
     LaunchShape L;
     long long slots = 0;
-    launch_shape(b, a.workspace != nullptr, L, slots);
+    launch_shape(b, true, L, slots);
+    if (L.ws_pieces > 0 && a.workspace == nullptr) launch_shape(b, false, L, slots);   // no room for piece records: nothing is cut
     const long long per_xcd = slots + (L.split ? EXTRA_PER_XCD : 0);
     const long long grid = NUM_XCD * per_xcd;
     if (grid > 0x3fffffff) return hipErrorInvalidValue;
@@ -1217,13 +1250,7 @@ hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream)
     else
         hipLaunchKernelGGL(attn_bf16_d128_kernel<false>, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, KernArgs{a, L});
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess || !L.split) return err;
-    // no context of this batch is long enough to be cut along the keys (two pieces of the usual minimum, or four
-    // short ones on an under-filled XCD): left-over units can only have been halved along their rows, which
-    // leaves nothing to merge
-    constexpr long long MIN_CUT_TILES = 2 * MIN_TILES_PER_PART < MIN_UNIT_TILES_UNDERFILLED ? 2 * MIN_TILES_PER_PART : MIN_UNIT_TILES_UNDERFILLED;
-    static_assert(4 * MIN_TILES_PER_PART_UNDERFILLED <= MIN_UNIT_TILES_UNDERFILLED, "short pieces come four or more at a time");
-    if (((long long)b.max_pages * b.page_size + BC - 1) / BC < MIN_CUT_TILES) return err;
+    if (err != hipSuccess || L.ws_pieces == 0) return err;              // nothing can have been cut along the keys
     hipLaunchKernelGGL(attn_bf16_merge_kernel, dim3(NUM_XCD * MERGE_PER_XCD), dim3(NTHREADS), 0, stream, a, L);
     return hipGetLastError();
 }

@@ -73,7 +73,7 @@ hipError_t launch_kv_scatter(const BatchView& b, const void* k_new, const void* 
                              void* v_cache, int elt_bytes, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_bf16_d128(const AttnArgs& a, hipStream_t stream);
-size_t attn_bf16_d128_workspace_bytes();   // what launch_attn_bf16_d128 wants behind AttnArgs::workspace
+size_t attn_bf16_d128_workspace_bytes(const BatchView& b);   // what launch_attn_bf16_d128 wants behind AttnArgs::workspace
 // host only: how launch_attn_bf16_d128 would lay the batch out (new_lens: host copy); arrays of 8 are per XCD
 void attn_bf16_d128_plan_host(const BatchView& b, const int32_t* new_lens, bool has_workspace, int32_t* shape6, long long* grid,
                               int32_t* units, int32_t* pieces, int32_t* uneven_k, int32_t* rows_only);

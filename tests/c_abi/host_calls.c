@@ -31,7 +31,10 @@ int main(void)
     b.dtype = EMM_BF16;
     b.softmax_scale = 0.088388f;
     CHECK(emm_version() > 0);
+    CHECK(emm_prefill_attn_workspace_size(&b, &bytes) == EMM_OK && bytes == 0);   /* contexts of 128 tokens: nothing is cut */
+    b.max_pages_per_req = 1024;
     CHECK(emm_prefill_attn_workspace_size(&b, &bytes) == EMM_OK && bytes > 0);
+    b.max_pages_per_req = 8;
     b.page_size = 24;
     CHECK(emm_prefill_attn_workspace_size(&b, &bytes) == EMM_ERR_UNSUPPORTED);
     b.page_size = 16;

@@ -47,7 +47,8 @@ def test_struct_layout_matches_header():
 
 
 def test_workspace_size_and_scalar_checks():
-    assert B.emm_prefill_attn_workspace_size(_batch()) > 0
+    assert B.emm_prefill_attn_workspace_size(_batch(num_pages=1024, max_pages_per_req=512)) > 0
+    assert B.emm_prefill_attn_workspace_size(_batch()) == 0          # contexts of at most 64 tokens: nothing to cut
     assert B.emm_prefill_attn_workspace_size(_batch(dtype="f32")) == 0
     lib = B.load()
     n = ctypes.c_size_t()
@@ -82,7 +83,7 @@ def test_attention_rejects_before_launch(entry):
     ok = 0x1000                      # fake, 16-byte aligned, never dereferenced: validation fails first
     b = _batch()                     # device arrays are NULL
     assert fn(ctypes.byref(b), ok, ok, ok, ok, None, None, 0, None) == B.EMM_ERR_NULL
-    b = _batch()
+    b = _batch(num_pages=1024, max_pages_per_req=512)
     b.page_table = b.prefix_lens = b.new_lens = b.cu_new_lens = ok
     need = B.emm_prefill_attn_workspace_size(b)
     assert need > 0                  # the bf16 kernels cut their last work units and merge them through it

@@ -785,6 +785,36 @@ def test_error_codes_on_device():
     assert e.value.status == B.EMM_ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("name,kind,H,Hkv,prefix,new", [
+    ("ws_cut32", "causal", 28, 4, [16384], [36]),                    # uniform: one unit per second XCD, 32 pieces: exact size
+    ("ws_ragged", "causal", 28, 4, [9000, 300, 5000], [64, 200, 36]),   # ragged: sized from bounds
+    ("ws_uneven", "cross", 32, 8, [6404] * 7, [600, 350, 700, 280, 512, 90, 768]),   # 22 units left over: two uneven pieces each
+])
+def test_workspace_of_exactly_the_stated_size_is_enough(name, kind, H, Hkv, prefix, new):
+    """The kernels must stay inside emm_prefill_attn_workspace_size bytes: a buffer of exactly that size followed by a
+    guard region, which must come back untouched, and the same output bits as with a roomy workspace."""
+    print("case", name, flush=True)
+    wl = W.build_workload(name, kind, "bf16", 2300 + len(name), num_q_heads=H, num_kv_heads=Hkv, head_dim=128,
+                          page_size=16, prefix_lens=prefix, new_lens=new)
+    ref = _gpu_run(wl)
+    _compare(wl, ref)
+    need = B.emm_prefill_attn_workspace_size(ref.batch)
+    assert need > 0
+    guard = 1 << 16
+    buf = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    dw = B.DeviceWorkload(wl)
+    dw.workspace = buf[:need]
+    dw.out.zero_()
+    dw.step()
+    torch.cuda.synchronize()
+    assert bool((buf[need:] == 0xA5).all()), "the kernels wrote past the stated workspace size"
+    assert B.DeviceWorkload.to_numpy_bits(dw.out).tobytes() == B.DeviceWorkload.to_numpy_bits(ref.out).tobytes()
+    too_small = buf[:need - 16]
+    with pytest.raises(B.EmmError) as e:
+        (B.emm_prefill_attn if kind == "causal" else B.emm_cross_attn)(dw.batch, dw.q, dw.k_cache, dw.v_cache, dw.out, dw.lse, too_small)
+    assert e.value.status == B.EMM_ERR_WORKSPACE
+
+
 def test_two_streams_with_their_own_workspaces():
     """The library keeps no state between calls: two batches stepped on two streams at the same time, each with
     its own workspace, give the bits they give when stepped one after the other.  (Both streams have the default

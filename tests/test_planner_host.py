@@ -101,6 +101,52 @@ def test_random_batches_match_model_and_keep_invariants(seed):
         assert (p["uneven_k"][x] > 0) <= (16 < rem <= 30)
 
 
+PIECE_BYTES = 66 * 512 * 4          # a piece record: 64 accumulator values, reference exponent and row sum per thread
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_workspace_size_covers_the_plan(seed):
+    """emm_prefill_attn_workspace_size, which sees only the scalar fields, against what the plan for the real lengths
+    needs: 8 XCDs x (left-over units x planned pieces) records, laid out with one stride for all XCDs.  It must cover
+    the plan for any lengths the scalars admit, be exact when the host can know the plan (all requests alike), and
+    be zero when nothing can be cut."""
+    rng = np.random.default_rng(900 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 4, 7, 8]))
+    n_req = int(rng.choice([1, 2, 3, 8, 16, 40]))
+    top = int(rng.choice([3, 40, 300, 2100]))
+    uniform = rng.random() < 0.4
+    new = [top] * n_req if uniform else [int(x) for x in rng.integers(0, top + 1, n_req)]
+    if sum(new) == 0:
+        new[0] = top
+    max_pages = int(rng.choice([16, 64, 600, 4096]))          # contexts of at most 256 .. 65536 tokens
+    b = B.make_batch(num_reqs=n_req, num_q_heads=Hkv * G, num_kv_heads=Hkv, head_dim=128, page_size=16, num_pages=1 << 20,
+                     max_pages_per_req=max_pages, total_new_tokens=int(sum(new)), max_new_len=int(max(new)), dtype="bf16",
+                     softmax_scale=0.1)
+    size = B.emm_prefill_attn_workspace_size(b)
+    p = B.emm_prefill_plan_host(b, new)
+    assert size % (XCDS * PIECE_BYTES) == 0
+    stride = size // (XCDS * PIECE_BYTES)                      # records per XCD
+    cuttable = max_pages * 16 >= 24 * 64                       # a context of 24 key tiles: the shortest that is ever cut
+    need = 0
+    for x in range(XCDS):
+        rem = p["units"][x] % CUS
+        if p["cutting"] and p["pieces"][x] > 1 and not p["rows_only"][x] and cuttable:
+            need = max(need, rem * p["pieces"][x])
+    assert stride >= need, (new, p, stride)
+    if not cuttable or not p["cutting"]:
+        assert size == 0
+    if len(set(new)) == 1:
+        assert stride == need                                   # the host knows every XCD's unit count
+    assert stride <= 64
+
+
+def test_workspace_of_the_headline_workload_is_empty():
+    cfg3 = W.config(3)
+    b = _batch(28, 4, cfg3.new_lens.tolist())
+    assert B.emm_prefill_attn_workspace_size(b) == 0          # 56 units per XCD, none cut: no records, no merge
+
+
 def test_argument_errors():
     lib = B.load()
     import ctypes
