@@ -1,7 +1,8 @@
 """Host logic of the prefill launch (emm_prefill_plan_host): how a batch is dealt to the XCDs, how many work
-units each gets, and how the units left over after full rounds are cut -- against a model written out here in
-plain Python, and against the invariants the kernels rely on (every unit appears once; the extra workgroups,
-the workspace slots and the merge workgroups suffice).  No GPU."""
+units each gets, and how the units left over after full rounds are cut.  What carries weight here are the
+invariants the kernels rely on (every unit appears once; the extra workgroups, the workspace records and the
+merge workgroups suffice; the workspace size covers any plan the scalar fields admit); the second writing-out of
+the rule in plain Python only guards against the C++ and the description drifting apart.  No GPU."""
 from __future__ import annotations
 
 import numpy as np
