@@ -179,6 +179,8 @@ CUT_CASES = [
      [int(x) for x in np.random.default_rng(6).integers(0, 400, 100)]),          # 400 pairs: 50 per XCD, one per lane of the scan
     ("too_many_pairs", "causal", 32, 8, [int(x) for x in np.random.default_rng(7).integers(0, 900, 70)],
      [int(x) for x in np.random.default_rng(8).integers(1, 300, 70)]),           # 560 pairs: 70 per XCD, no scan, no cuts
+    ("far_too_many_pairs", "causal", 8, 8, [int(x) for x in np.random.default_rng(11).integers(0, 200, 280)],
+     [int(x) for x in np.random.default_rng(12).integers(0, 40, 280)]),          # 2240 pairs: 280 per XCD, some requests empty
     ("long_and_empty", "causal", 16, 16, [40, 0, 7, 5000], [0, 0, 0, 700]),     # 16 KV heads: two pairs of a request per XCD
     ("halve_ragged", "causal", 28, 4, [300, 1056, 0, 77], [100, 37, 150, 3]),   # last row tiles of 188, 3, 26, 21 rows
 ]
