@@ -22,6 +22,9 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # published dense bf16 MFMA figure of MI355X 
 HBM_PEAK_GBS = 8000.0
 
 
+W_PREFILL_SHARED = ("prefill_shared_video_b8_n12", "prefill_shared_video_b32_n4", "prefill_shared_image_b32")
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -112,7 +115,7 @@ PREFILL_SOURCES = ("attn_bf16.hip", "attn_bf16_common.h", "emm_internal.h")
 DECODE_SOURCES = ("attn_bf16_decode.hip", "attn_bf16_common.h", "emm_internal.h")
 
 
-def bench_timeline(workload):
+def bench_timeline(workload, suffix=None, prefill_shared=None):
     """One launch of the prefill kernel built with -DEMM_TIMELINE (python -m paper_2507_10069_amd.build --timeline):
     every workgroup leaves start / end time stamps (100 MHz), its shader cycle count, its key tiles and where it ran
     (XCC_ID, HW_ID); printed as a summary per round of workgroups and per XCD."""
@@ -125,7 +128,8 @@ def bench_timeline(workload):
         sys.exit("bench.py --timeline: build the instrumented library first: python -m paper_2507_10069_amd.build --timeline")
     B.LIB_PATH = hip_build.TIMELINE_LIB
     n_rec = 16384
-    wl = W.config(workload)
+    wl = (W.suffix_config(suffix) if suffix is not None else
+          W.prefill_shared_config(prefill_shared) if prefill_shared is not None else W.config(workload))
     dw = B.DeviceWorkload(wl)
     if dw.workspace is None or dw.workspace.numel() < n_rec * 64:
         sys.exit("bench.py --timeline: the instrumented library was not loaded")
@@ -326,11 +330,14 @@ def main():
     ap.add_argument("--suffix", default=None, metavar="NAME",
                     help="time one short-suffix prefill workload instead (the batch a large cache hit leaves): "
                          "suffix_b1_16k_n36, suffix_b8_16k_n36, suffix_b8_16k_n4 or suffix_b32_4k_n36")
+    ap.add_argument("--prefill-shared", default=None, metavar="NAME",
+                    help="time a prefill batch with shared prefix pages (%s): emm_prefill_attn against "
+                         "emm_prefill_attn_shared" % ", ".join(W_PREFILL_SHARED))
     ap.add_argument("--kv-migrate", action="store_true",
                     help="time the KV page migration primitive (pack and unpack with checksums) instead")
     ap.add_argument("--timeline", action="store_true",
-                    help="per-workgroup timeline of one prefill launch of --workload (needs the build made by "
-                         "python -m paper_2507_10069_amd.build --timeline)")
+                    help="per-workgroup timeline of one plain prefill launch on the batch that --workload, --suffix or "
+                         "--prefill-shared names (needs the build made by python -m paper_2507_10069_amd.build --timeline)")
     ap.add_argument("--prefix-cache", action="store_true",
                     help="time the host-side prefix cache (no GPU work) on a synthetic request stream")
     args = ap.parse_args()
@@ -348,7 +355,7 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     if args.timeline:
-        return bench_timeline(args.workload)
+        return bench_timeline(args.workload, args.suffix, args.prefill_shared)
     B.load()                                            # fails loudly if libemm.so has not been built
 
     if args.copy_calibration:
@@ -384,6 +391,40 @@ def main():
                        "parallelism": "single-gpu"},
             "new_tokens_per_s": wl.total_new_tokens / (ms * 1e-3), "attention_ms": attn_ms, "scatter_ms": scat_ms,
             "roofline": roof,
+        }), flush=True)
+        return
+    if args.prefill_shared is not None:
+        wl = W.prefill_shared_config(args.prefill_shared)
+        dw = B.DeviceWorkload(wl)
+        ms, attn_ms, scat_ms = time_workload(dw, args.steps, args.warmup)
+        keeps = dw.plan_prefill_shared()["num_groups"] > 0          # what the planner does with its default threshold
+        plan = dw.plan_prefill_shared(min_saved_key_tiles=0)        # timed with the groups in any case
+        ms_s, attn_s, scat_s = time_workload(dw, args.steps, args.warmup, dw.attention_prefill_shared)
+        flops = wl.attention_flops()
+        log("workload %s: plain %.4f ms/step (attention %.4f ms); %d sharing groups, row tiles %d -> %d, key tiles %d -> %d: "
+            "%.4f ms/step (attention %.4f ms, %.2fx); by default the planner %s the groups"
+            % (wl.name, ms, attn_ms, plan["num_groups"], plan["rows_tiles_plain"], plan["rows_tiles_shared"],
+               plan["key_tiles_plain"], plan["key_tiles_shared"], ms_s, attn_s, attn_ms / attn_s, "keeps" if keeps else "gives up"))
+        tflops = flops / (attn_s * 1e-3) / 1e12
+        distinct_gbs = wl.kv_distinct_read_bytes() / (attn_s * 1e-3) / 1e9
+        mfma_frac, hbm_frac = tflops / BF16_MFMA_PEAK_TFLOPS, distinct_gbs / HBM_PEAK_GBS
+        roof = ({"bound": "mfma", "achieved": tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac}
+                if mfma_frac >= hbm_frac else
+                {"bound": "hbm", "achieved": distinct_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac})
+        roof.update({"traffic": None, "kernel": "attn_bf16_d128_kernel (two passes) + attn_bf16_merge_kernel + attn_merge_parts_kernel"})
+        print(json.dumps({
+            "metric": "prefill_attention_tflops", "value": flops / (ms_s * 1e-3) / 1e12, "unit": "TFLOP/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_s, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+            "config": {"workload": wl.name, "requests": wl.num_reqs, "total_new_tokens": wl.total_new_tokens,
+                       "algorithmic_flops_per_step": flops, "kv_distinct_bytes_per_step": wl.kv_distinct_read_bytes(),
+                       "parallelism": "single-gpu"},
+            "new_tokens_per_s": wl.total_new_tokens / (ms_s * 1e-3), "attention_ms": attn_s, "scatter_ms": scat_s,
+            "sharing_groups": plan["num_groups"], "row_tiles_plain": plan["rows_tiles_plain"],
+            "row_tiles_shared": plan["rows_tiles_shared"], "key_tiles_plain": plan["key_tiles_plain"],
+            "key_tiles_shared": plan["key_tiles_shared"], "planner_default_keeps_groups": keeps,
+            "plain_path": {"ms_per_step": ms, "attention_ms": attn_ms},
+            "speedup_over_plain_attention": attn_ms / attn_s, "roofline": roof,
         }), flush=True)
         return
     if args.decode is not None:

@@ -163,6 +163,62 @@ emm_status emm_decode_attn_static(const emm_batch *batch, const void *q, const v
                                   const void *v_cache, void *out, float *lse, void *hip_stream);
 
 /*
+ * Prefill with shared prefixes (Section 3.3: requests repeat system prompts, images and videos, so several requests
+ * of a prefill batch hold the SAME physical pages at the head of their page tables).  When such requests bring few
+ * new tokens each (a short question about a video seen before), every one of them on its own fills a small part
+ * of a 256-row work unit and streams the whole shared context for it.  Here the query rows of a sharing GROUP are
+ * packed into common row tiles for the shared keys, which are then streamed once per group and row tile; each
+ * request's remaining keys (the rest of its cached prefix and its new tokens, causal) are done per request; and the
+ * two partial results of every row are merged by their softmax denominators -- the same attention as
+ * emm_prefill_attn up to rounding (both partial outputs pass through bf16).
+ *
+ * emm_prefill_shared_plan_host finds the groups from HOST copies of the batch arrays (runs of consecutive requests
+ * whose page tables agree on their leading pages; shared length a multiple of 64 tokens, at least
+ * max(min_shared_tokens, 64); a group is formed only if its packed rows need fewer 256-row tiles than its members
+ * apart).  The three steps cost two more kernel launches and a second pass over every output row than the one plain
+ * call, so groups are only worth having when they save enough streaming: with key_tiles_plain / key_tiles_shared
+ * the 64-key tiles that all 256-row work units together stream without and with the groups, the plan keeps its
+ * groups only if key_tiles_plain - key_tiles_shared >= min_saved_key_tiles (0: always; negative: the library's
+ * default, EMM_PREFILL_SHARED_MIN_SAVED_KEY_TILES, measured on MI355X on batches of 8 .. 32 requests).  It writes,
+ * into host arrays the caller provides, what the two passes need:
+ *   req_shared_len    [B]                        tokens of request r done in its group's pass; 0: in no group
+ *   group_page_table  [B / 2][max_pages_per_req] page-table row of each group's first member
+ *   group_prefix_lens, group_new_lens [B / 2]    shared length; new tokens of all members together
+ *   group_cu_new_lens [B / 2 + 1]                first packed row of each group (members are consecutive)
+ *   own_page_table    [B][max_pages_per_req]     each request's row moved left by the pages of its shared part
+ *   own_prefix_lens   [B]                        prefix_lens[r] - req_shared_len[r]
+ * and fills the scalar fields of two descriptors, `groups` (one "request" per group) and `own` (the batch itself
+ * with the moved page table), whose four array pointers it leaves NULL: the caller copies the arrays to the
+ * device and sets them (own.new_lens and own.cu_new_lens are the batch's).  num_groups == 0: nothing to gain, use
+ * emm_prefill_attn (req_shared_len is then all zero and `own` is the batch as it was).  rows_tiles_plain /
+ * rows_tiles_shared: 256-row tiles per KV head over the shared keys without and with the groups; they and the two
+ * key-tile counts describe the grouping that was found, also when it was then given up as not worth it.
+ *
+ * emm_prefill_attn_shared runs the three steps on the stream: the groups' pass (unmasked, into the workspace), the
+ * own pass (emm_prefill_attn of `own`, into out), the merge (into out and lse).  emm_kv_scatter of the ORIGINAL
+ * batch must precede it.  req_shared_len: device [B].  Workspace: emm_prefill_attn_shared_workspace_size, 256-byte
+ * aligned.  EMM_BF16 only.
+ */
+#define EMM_PREFILL_SHARED_MIN_SAVED_KEY_TILES 10000
+typedef struct {
+    int32_t num_groups;
+    int64_t rows_tiles_plain, rows_tiles_shared;
+    int64_t key_tiles_plain, key_tiles_shared;
+    emm_batch groups, own;
+    int32_t *req_shared_len;
+    int32_t *group_page_table, *group_prefix_lens, *group_new_lens, *group_cu_new_lens;
+    int32_t *own_page_table, *own_prefix_lens;
+} emm_prefill_shared_plan;
+emm_status emm_prefill_shared_plan_host(const emm_batch *batch, const int32_t *host_page_table,
+                                        const int32_t *host_prefix_lens, const int32_t *host_new_lens,
+                                        const int32_t *host_cu_new_lens, int32_t min_shared_tokens,
+                                        int64_t min_saved_key_tiles, emm_prefill_shared_plan *plan);
+emm_status emm_prefill_attn_shared_workspace_size(const emm_batch *groups, const emm_batch *own, size_t *bytes);
+emm_status emm_prefill_attn_shared(const emm_batch *groups, const emm_batch *own, const int32_t *req_shared_len,
+                                   const void *q, const void *k_cache, const void *v_cache, void *out, float *lse,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Decode step with shared prefixes (Section 3.3: requests repeat system prompts and images, so in a decode
  * batch several requests hold the SAME physical pages at the head of their page tables; Section 2.2: the
  * step is bound by reading K/V).  A unit is a run of consecutive requests of the batch together with the

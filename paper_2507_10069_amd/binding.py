@@ -20,10 +20,12 @@ LIB_PATH = os.environ.get("EMM_LIB_PATH") or os.path.join(HERE, "libemm.so")
 EMM_OK, EMM_ERR_NULL, EMM_ERR_INVALID_ARG, EMM_ERR_UNSUPPORTED, EMM_ERR_WORKSPACE, EMM_ERR_LAUNCH = range(6)
 EMM_F32, EMM_BF16 = 0, 1
 EMM_DECODE_STATIC_SCRATCH_BYTES = 16 << 20
+EMM_PREFILL_SHARED_MIN_SAVED_KEY_TILES = 10000
 
 EXPORTS = ["emm_kv_scatter", "emm_prefill_attn_workspace_size", "emm_prefill_attn", "emm_cross_attn", "emm_decode_attn",
            "emm_decode_attn_static", "emm_decode_attn_shared_workspace_size", "emm_decode_attn_shared", "emm_shared_prefix_plan_host",
            "emm_cross_attn_shared", "emm_decode_step", "emm_kv_pages_pack", "emm_kv_pages_unpack",
+           "emm_prefill_shared_plan_host", "emm_prefill_attn_shared_workspace_size", "emm_prefill_attn_shared",
            "emm_validate_batch_host", "emm_prefill_plan_host", "emm_status_string", "emm_version"]
 
 
@@ -47,6 +49,14 @@ class emm_prefill_plan(ctypes.Structure):
                 ("cutting", ctypes.c_int32), ("uneven", ctypes.c_int32), ("slots_per_xcd", ctypes.c_int32),
                 ("grid", ctypes.c_int64), ("units", ctypes.c_int32 * 8), ("pieces", ctypes.c_int32 * 8),
                 ("uneven_k", ctypes.c_int32 * 8), ("rows_only", ctypes.c_int32 * 8)]
+
+
+class emm_prefill_shared_plan(ctypes.Structure):
+    _fields_ = [("num_groups", ctypes.c_int32), ("rows_tiles_plain", ctypes.c_int64), ("rows_tiles_shared", ctypes.c_int64),
+                ("key_tiles_plain", ctypes.c_int64), ("key_tiles_shared", ctypes.c_int64),
+                ("groups", emm_batch), ("own", emm_batch), ("req_shared_len", ctypes.c_void_p),
+                ("group_page_table", ctypes.c_void_p), ("group_prefix_lens", ctypes.c_void_p), ("group_new_lens", ctypes.c_void_p),
+                ("group_cu_new_lens", ctypes.c_void_p), ("own_page_table", ctypes.c_void_p), ("own_prefix_lens", ctypes.c_void_p)]
 
 
 class emm_shared_prefix(ctypes.Structure):
@@ -93,6 +103,13 @@ def load() -> ctypes.CDLL:
     lib.emm_cross_attn_shared.argtypes = lib.emm_decode_attn_shared.argtypes
     lib.emm_decode_step.restype = ctypes.c_int
     lib.emm_decode_step.argtypes = [bp, ctypes.POINTER(emm_shared_prefix)] + [vp] * 8 + [ctypes.c_size_t, vp]
+    lib.emm_prefill_shared_plan_host.restype = ctypes.c_int
+    lib.emm_prefill_shared_plan_host.argtypes = [bp, i32p, i32p, i32p, i32p, ctypes.c_int32, ctypes.c_int64,
+                                                 ctypes.POINTER(emm_prefill_shared_plan)]
+    lib.emm_prefill_attn_shared_workspace_size.restype = ctypes.c_int
+    lib.emm_prefill_attn_shared_workspace_size.argtypes = [bp, bp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.emm_prefill_attn_shared.restype = ctypes.c_int
+    lib.emm_prefill_attn_shared.argtypes = [bp, bp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.emm_kv_pages_pack.restype = ctypes.c_int
     lib.emm_kv_pages_pack.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, vp, ctypes.c_int32, vp, vp, vp]
     lib.emm_kv_pages_unpack.restype = ctypes.c_int
@@ -260,6 +277,53 @@ def emm_shared_prefix_plan_host(batch: emm_batch, page_table: np.ndarray, prefix
             "req_unit": outs[3][:B_], "req_shared_len": outs[4][:B_]}
 
 
+def emm_prefill_shared_plan_host(batch: emm_batch, page_table: np.ndarray, prefix_lens: np.ndarray, new_lens: np.ndarray,
+                                 cu_new_lens: np.ndarray, min_shared_tokens: int = 64, min_saved_key_tiles: int = -1) -> dict:
+    """Returns the plan's host arrays (cut to the number of groups), its counts and the two descriptors with their
+    scalar fields filled (array pointers unset).  min_saved_key_tiles: 0 keeps every group that saves a row tile,
+    negative stands for the library's default threshold."""
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    ins = [np.ascontiguousarray(a, dtype=np.int32) for a in (page_table, prefix_lens, new_lens, cu_new_lens)]
+    B_, mp = int(batch.num_reqs), int(batch.max_pages_per_req)
+    half = max(B_ // 2, 1)
+    arr = {"req_shared_len": np.zeros(max(B_, 1), np.int32), "group_page_table": np.full((half, max(mp, 1)), -1, np.int32),
+           "group_prefix_lens": np.zeros(half, np.int32), "group_new_lens": np.zeros(half, np.int32),
+           "group_cu_new_lens": np.zeros(half + 1, np.int32), "own_page_table": np.full((max(B_, 1), max(mp, 1)), -1, np.int32),
+           "own_prefix_lens": np.zeros(max(B_, 1), np.int32)}
+    plan = emm_prefill_shared_plan()
+    for k, a in arr.items():
+        setattr(plan, k, a.ctypes.data)
+    _check(load().emm_prefill_shared_plan_host(ctypes.byref(batch), *[a.ctypes.data_as(i32p) for a in ins], min_shared_tokens,
+                                               min_saved_key_tiles, ctypes.byref(plan)), "emm_prefill_shared_plan_host")
+    NG = int(plan.num_groups)
+    out = {"num_groups": NG, "rows_tiles_plain": int(plan.rows_tiles_plain), "rows_tiles_shared": int(plan.rows_tiles_shared),
+           "key_tiles_plain": int(plan.key_tiles_plain), "key_tiles_shared": int(plan.key_tiles_shared),
+           "req_shared_len": arr["req_shared_len"][:B_], "group_page_table": arr["group_page_table"][:max(NG, 1)],
+           "group_prefix_lens": arr["group_prefix_lens"][:max(NG, 1)], "group_new_lens": arr["group_new_lens"][:max(NG, 1)],
+           "group_cu_new_lens": arr["group_cu_new_lens"][:max(NG, 1) + 1], "own_page_table": arr["own_page_table"][:B_],
+           "own_prefix_lens": arr["own_prefix_lens"][:B_]}
+    groups, own = emm_batch(), emm_batch()
+    ctypes.memmove(ctypes.byref(groups), ctypes.byref(plan.groups), ctypes.sizeof(emm_batch))
+    ctypes.memmove(ctypes.byref(own), ctypes.byref(plan.own), ctypes.sizeof(emm_batch))
+    out["groups"], out["own"] = groups, own
+    return out
+
+
+def emm_prefill_attn_shared_workspace_size(groups: emm_batch, own: emm_batch) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().emm_prefill_attn_shared_workspace_size(ctypes.byref(groups), ctypes.byref(own), ctypes.byref(n)),
+           "emm_prefill_attn_shared_workspace_size")
+    return int(n.value)
+
+
+def emm_prefill_attn_shared(groups: emm_batch, own: emm_batch, req_shared_len, q, k_cache, v_cache, out, lse=None,
+                            workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    _check(load().emm_prefill_attn_shared(ctypes.byref(groups), ctypes.byref(own), _ptr(req_shared_len), _ptr(q), _ptr(k_cache),
+                                          _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)),
+           "emm_prefill_attn_shared")
+
+
 def emm_kv_pages_pack(k_cache, v_cache, num_pages: int, page_bytes: int, page_ids, n: int, staging, checksums=None,
                       stream=None) -> None:
     _check(load().emm_kv_pages_pack(_ptr(k_cache), _ptr(v_cache), num_pages, page_bytes, _ptr(page_ids), n,
@@ -341,6 +405,29 @@ class DeviceWorkload:
         self.shared_workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=self.device)
         self.shared_plan = plan
         return plan
+
+    def plan_prefill_shared(self, min_shared_tokens: int = 64, min_saved_key_tiles: int = -1) -> dict:
+        """Find the sharing groups of a prefill batch (host), move what the two passes need to the device and finish
+        the two descriptors."""
+        import torch
+        wl = self.wl
+        plan = emm_prefill_shared_plan_host(self.batch, wl.page_table, wl.prefix_lens, wl.new_lens, wl.cu_new_lens, min_shared_tokens,
+                                            min_saved_key_tiles)
+        dev = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.device) for k, v in plan.items() if isinstance(v, np.ndarray)}
+        groups, own = plan["groups"], plan["own"]
+        groups.page_table, groups.prefix_lens = _ptr(dev["group_page_table"]), _ptr(dev["group_prefix_lens"])
+        groups.new_lens, groups.cu_new_lens = _ptr(dev["group_new_lens"]), _ptr(dev["group_cu_new_lens"])
+        own.page_table, own.prefix_lens = _ptr(dev["own_page_table"]), _ptr(dev["own_prefix_lens"])
+        own.new_lens, own.cu_new_lens = _ptr(self.new_lens), _ptr(self.cu_new_lens)
+        self.prefill_shared = {"plan": plan, "dev": dev, "groups": groups, "own": own}
+        ws = emm_prefill_attn_shared_workspace_size(groups, own)
+        self.prefill_shared["workspace"] = torch.empty(max(ws, 256), dtype=torch.uint8, device=self.device)
+        return plan
+
+    def attention_prefill_shared(self, stream=None) -> None:
+        ps = self.prefill_shared
+        emm_prefill_attn_shared(ps["groups"], ps["own"], ps["dev"]["req_shared_len"], self.q, self.k_cache, self.v_cache,
+                                self.out, self.lse, ps["workspace"], stream)
 
     def decode_step(self, shared: bool = False, stream=None) -> None:
         """Scatter + decode attention in one call (emm_decode_step), with the planned units or without."""

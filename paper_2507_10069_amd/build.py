@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libemm.so")
-SOURCES = ["api.hip", "kv_scatter.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_decode.hip", "kv_migrate.hip", "prefix_cache.cpp"]
+SOURCES = ["api.hip", "kv_scatter.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_decode.hip", "attn_merge.hip", "kv_migrate.hip", "prefix_cache.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instruction forms are switched off for every device translation unit
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

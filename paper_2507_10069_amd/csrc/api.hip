@@ -327,6 +327,207 @@ emm_status emm_shared_prefix_plan_host(const emm_batch* b, const int32_t* pt, co
     return EMM_OK;
 }
 
+// ---- prefill with shared prefixes: the shared keys once per sharing group, each request's own keys, then the merge
+
+namespace {
+
+size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
+
+// do the two descriptors describe the two passes of one batch?
+emm_status check_shared_pair(const emm_batch* groups, const emm_batch* own)
+{
+    emm_status st = check_scalars(groups);
+    if (st != EMM_OK) return st;
+    st = check_scalars(own);
+    if (st != EMM_OK) return st;
+    st = check_supported(own);
+    if (st != EMM_OK) return st;
+    if (own->dtype != EMM_BF16 || groups->dtype != EMM_BF16) return EMM_ERR_UNSUPPORTED;
+    if (groups->num_q_heads != own->num_q_heads || groups->num_kv_heads != own->num_kv_heads || groups->head_dim != own->head_dim ||
+        groups->page_size != own->page_size || groups->num_pages != own->num_pages || groups->softmax_scale != own->softmax_scale ||
+        groups->total_new_tokens != own->total_new_tokens || groups->num_reqs > own->num_reqs)
+        return EMM_ERR_INVALID_ARG;
+    return EMM_OK;
+}
+
+struct SharedWorkspace {
+    size_t out_shared, lse_shared, lse_own, inner, inner_bytes, total;
+};
+
+emm_status shared_workspace(const emm_batch* groups, const emm_batch* own, SharedWorkspace* w)
+{
+    const size_t rows = static_cast<size_t>(own->total_new_tokens) * own->num_q_heads;
+    size_t a = 0, c = 0;
+    emm_status st = emm_prefill_attn_workspace_size(groups, &a);
+    if (st != EMM_OK) return st;
+    st = emm_prefill_attn_workspace_size(own, &c);
+    if (st != EMM_OK) return st;
+    w->out_shared = 0;
+    w->lse_shared = align256(rows * own->head_dim * 2);
+    w->lse_own = w->lse_shared + align256(rows * 4);
+    w->inner = w->lse_own + align256(rows * 4);
+    w->inner_bytes = std::max(a, c);                         // the two attention passes run one after the other
+    w->total = w->inner + align256(w->inner_bytes);
+    return EMM_OK;
+}
+
+}  // namespace
+
+extern "C" emm_status emm_prefill_attn_shared_workspace_size(const emm_batch* groups, const emm_batch* own, size_t* bytes)
+{
+    if (bytes == nullptr) return EMM_ERR_NULL;
+    *bytes = 0;
+    emm_status st = check_shared_pair(groups, own);
+    if (st != EMM_OK) return st;
+    SharedWorkspace w;
+    st = shared_workspace(groups, own, &w);
+    if (st != EMM_OK) return st;
+    *bytes = w.total;
+    return EMM_OK;
+}
+
+extern "C" emm_status emm_prefill_attn_shared(const emm_batch* groups, const emm_batch* own, const int32_t* req_shared_len,
+                                               const void* q, const void* k_cache, const void* v_cache, void* out, float* lse,
+                                               void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    emm_status st = check_shared_pair(groups, own);
+    if (st != EMM_OK) return st;
+    SharedWorkspace w;
+    st = shared_workspace(groups, own, &w);
+    if (st != EMM_OK) return st;
+    if (own->num_reqs == 0 || own->total_new_tokens == 0) return EMM_OK;
+    if (req_shared_len == nullptr || workspace == nullptr) return EMM_ERR_NULL;
+    if (workspace_bytes < w.total) return EMM_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return EMM_ERR_INVALID_ARG;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    float* lse_own = reinterpret_cast<float*>(ws + w.lse_own);
+    void* inner = w.inner_bytes > 0 ? ws + w.inner : nullptr;
+    // 1. every group's rows over the group's shared keys: no mask (all of them precede every new token), rows of all
+    //    members packed into common row tiles
+    if (groups->num_reqs > 0) {
+        st = attention(groups, q, k_cache, v_cache, ws + w.out_shared, reinterpret_cast<float*>(ws + w.lse_shared), inner,
+                       w.inner_bytes, hip_stream, 0);
+        if (st != EMM_OK) return st;
+    }
+    // 2. every request over its own keys (what its page table holds behind the shared part), causal
+    st = attention(own, q, k_cache, v_cache, out, lse_own, inner, w.inner_bytes, hip_stream, 1);
+    if (st != EMM_OK) return st;
+    // 3. the members' rows: both parts into one
+    const hipError_t err = emm::launch_attn_merge_parts(view_of(own), req_shared_len, ws + w.out_shared,
+                                                        reinterpret_cast<const float*>(ws + w.lse_shared), lse_own, out, lse,
+                                                        static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? EMM_OK : EMM_ERR_LAUNCH;
+}
+
+extern "C" emm_status emm_prefill_shared_plan_host(const emm_batch* b, const int32_t* pt, const int32_t* prefix,
+                                                    const int32_t* new_lens, const int32_t* cu, int32_t min_shared_tokens,
+                                                    int64_t min_saved_key_tiles, emm_prefill_shared_plan* plan)
+{
+    emm_status st = check_scalars(b);
+    if (st != EMM_OK) return st;
+    st = check_supported(b);                                  // page sizes that divide, or are divided by, a key tile
+    if (st != EMM_OK) return st;
+    if (plan == nullptr) return EMM_ERR_NULL;
+    plan->num_groups = 0;
+    plan->rows_tiles_plain = plan->rows_tiles_shared = 0;
+    plan->key_tiles_plain = plan->key_tiles_shared = 0;
+    plan->groups = *b;
+    plan->own = *b;
+    plan->groups.page_table = plan->groups.prefix_lens = plan->groups.new_lens = plan->groups.cu_new_lens = nullptr;
+    plan->own.page_table = plan->own.prefix_lens = plan->own.new_lens = plan->own.cu_new_lens = nullptr;
+    plan->groups.num_reqs = 0;
+    plan->groups.max_new_len = 0;
+    if (b->num_reqs == 0) return EMM_OK;
+    if (pt == nullptr || prefix == nullptr || new_lens == nullptr || cu == nullptr || plan->req_shared_len == nullptr ||
+        plan->group_page_table == nullptr || plan->group_prefix_lens == nullptr || plan->group_new_lens == nullptr ||
+        plan->group_cu_new_lens == nullptr || plan->own_page_table == nullptr || plan->own_prefix_lens == nullptr)
+        return EMM_ERR_NULL;
+    const int B = b->num_reqs, ps = b->page_size, G = b->num_q_heads / b->num_kv_heads;
+    const int64_t mp = b->max_pages_per_req;
+    const int64_t floor_len = std::max<int64_t>(min_shared_tokens, 64);
+    auto tiles = [&](int64_t n_new) { return (n_new * G + 255) / 256; };       // row tiles of 256 rows per KV head
+    // tokens that requests i and j share: leading equal page-table entries, as far as both requests' cached tokens
+    // fill the page
+    auto common = [&](int i, int j) -> int64_t {
+        const int64_t full = std::min(prefix[i], prefix[j]) / ps;
+        const int32_t* x = pt + static_cast<int64_t>(i) * mp;
+        const int32_t* y = pt + static_cast<int64_t>(j) * mp;
+        int64_t p = 0;
+        while (p < full && p < mp && x[p] == y[p]) ++p;
+        return p * ps;
+    };
+    int NG = 0;
+    int64_t plain = 0, shared_tiles = 0;
+    for (int r = 0; r < B; ++r) plan->req_shared_len[r] = 0;
+    for (int i = 0; i < B;) {
+        int n = 1;
+        int64_t S = 0, sum_new = new_lens[i], before = tiles(new_lens[i]);
+        if (new_lens[i] > 0) {
+            int64_t cur = INT64_MAX;
+            for (int j = i + 1; j < B && new_lens[j] > 0; ++j) {
+                const int64_t cand = std::min(cur, common(i, j)) / 64 * 64;     // whole key tiles
+                if (cand < floor_len) break;
+                // what a group saves: row tiles (the packed rows need fewer than the members' own) times the keys they
+                // no longer stream; one more member must not lower that
+                const int64_t saved_now = (before - tiles(sum_new)) * S;
+                const int64_t saved_then = (before + tiles(new_lens[j]) - tiles(sum_new + new_lens[j])) * cand;
+                if (n > 1 && saved_then < saved_now) break;
+                cur = S = cand;
+                sum_new += new_lens[j];
+                before += tiles(new_lens[j]);
+                ++n;
+            }
+        }
+        const bool pays = n >= 2 && tiles(sum_new) < before;
+        if (pays) {
+            for (int r = i; r < i + n; ++r) plan->req_shared_len[r] = static_cast<int32_t>(S);
+            std::copy(pt + static_cast<int64_t>(i) * mp, pt + static_cast<int64_t>(i + 1) * mp, plan->group_page_table + NG * mp);
+            plan->group_prefix_lens[NG] = static_cast<int32_t>(S);
+            plan->group_new_lens[NG] = static_cast<int32_t>(sum_new);
+            plan->group_cu_new_lens[NG] = cu[i];
+            plan->groups.max_new_len = std::max<int32_t>(plan->groups.max_new_len, static_cast<int32_t>(sum_new));
+            shared_tiles += tiles(sum_new);
+            ++NG;
+        } else {
+            n = 1;
+        }
+        for (int r = i; r < i + n; ++r) plain += tiles(new_lens[r]);
+        i += n;
+    }
+    // 64-key tiles that the batch's work units stream (per KV head a request has tiles(new) units, each over the
+    // request's whole context, taken as prefix + new for all of them), without the groups and with them
+    int64_t keys_plain = 0, keys_shared = 0;
+    for (int r = 0; r < B; ++r) {
+        const int64_t ctx = static_cast<int64_t>(prefix[r]) + new_lens[r], S = plan->req_shared_len[r];
+        keys_plain += tiles(new_lens[r]) * ((ctx + 63) / 64);
+        keys_shared += tiles(new_lens[r]) * ((ctx - S + 63) / 64);
+    }
+    for (int g = 0; g < NG; ++g) keys_shared += tiles(plan->group_new_lens[g]) * (plan->group_prefix_lens[g] / 64);
+    plan->key_tiles_plain = keys_plain * b->num_kv_heads;
+    plan->key_tiles_shared = keys_shared * b->num_kv_heads;
+    if (min_saved_key_tiles < 0) min_saved_key_tiles = EMM_PREFILL_SHARED_MIN_SAVED_KEY_TILES;
+    if (NG > 0 && plan->key_tiles_plain - plan->key_tiles_shared < min_saved_key_tiles) {
+        // not worth two more launches and a second pass over the outputs
+        NG = 0;
+        plan->groups.max_new_len = 0;
+        for (int r = 0; r < B; ++r) plan->req_shared_len[r] = 0;
+    }
+    plan->group_cu_new_lens[NG] = b->total_new_tokens;
+    // every request's own part: its page-table row moved left by the pages of the shared part
+    for (int r = 0; r < B; ++r) {
+        const int64_t skip = plan->req_shared_len[r] / ps;
+        int32_t* row = plan->own_page_table + static_cast<int64_t>(r) * mp;
+        const int32_t* src = pt + static_cast<int64_t>(r) * mp;
+        for (int64_t p = 0; p < mp; ++p) row[p] = p + skip < mp ? src[p + skip] : -1;
+        plan->own_prefix_lens[r] = prefix[r] - plan->req_shared_len[r];
+    }
+    plan->num_groups = NG;
+    plan->groups.num_reqs = NG;
+    plan->rows_tiles_plain = plain;
+    plan->rows_tiles_shared = shared_tiles;
+    return EMM_OK;
+}
+
 static emm_status check_pages_args(const void* k_cache, const void* v_cache, const void* staging,
                                    const int32_t* page_ids, int32_t n, int32_t num_pages, int64_t page_bytes,
                                    const void* c0, const void* c1, const void* c2)

@@ -91,6 +91,11 @@ hipError_t launch_attn_bf16_decode_shared(const AttnArgs& a, const SharedPrefixV
 // the same, fused with the scatter of the query tokens' own K/V rows (a.k_new, a.v_new; pools writable; causal)
 hipError_t launch_attn_bf16_decode_step(const AttnArgs& a, const SharedPrefixView& sv, hipStream_t stream);
 
+// merge of two attention results of the same rows over disjoint key sets (prefill with shared prefixes): out and lse
+// hold the second part on entry and the merged result on return; rows of requests with req_shared_len <= 0 stay
+hipError_t launch_attn_merge_parts(const BatchView& b, const int32_t* req_shared_len, const void* out_shared,
+                                   const float* lse_shared, const float* lse_own, void* out, float* lse, hipStream_t stream);
+
 // KV page migration: pack (pools -> staging) or unpack (staging -> pools) n pages with a checksum per page
 hipError_t launch_kv_pages(bool unpack, void* k_cache, void* v_cache, void* staging, const int32_t* page_ids, int n,
                            int num_pages, long long page_bytes, uint32_t* checksums, const uint32_t* expected,

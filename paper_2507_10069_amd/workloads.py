@@ -373,6 +373,35 @@ def suffix_config(name: str, shrink: int = 1) -> Workload:
                           prefix_lens=[_s(P, shrink)] * n_req, new_lens=[N] * n_req, spare_pages=8)
 
 
+def prefill_shared_config(name: str, shrink: int = 1) -> Workload:
+    """Prefill batches whose requests hold the same physical pages at the head of their page tables (Section 3.3:
+    questions about one video or image, one system prompt): a long shared cached part, then what each request
+    cached alone, then a short new suffix.  Few rows per request, so the rows of a sharing group fill row tiles
+    that single requests leave mostly empty.
+      prefill_shared_video_b8_n12   8 requests about one video: 16384 shared tokens, 12 new tokens each, 28/4 heads
+      prefill_shared_video_b32_n4   8 videos with 4 requests each, 16384 shared tokens, 4 new tokens each, 28/4 heads
+      prefill_shared_image_b32      32 requests in 4 groups of 8 sharing 2880 tokens (system prompt + image), then
+                                    0..600 cached tokens of their own and 6..40 new ones, 32/8 heads"""
+    if name == "prefill_shared_video_b8_n12":
+        shared, H, Hkv, seed = _s(16384, shrink), 28, 4, 2201
+        prefix, new, group = [shared] * 8, [12] * 8, [0] * 8
+    elif name == "prefill_shared_video_b32_n4":
+        shared, H, Hkv, seed = _s(16384, shrink), 28, 4, 2202
+        prefix, new, group = [shared] * 32, [4] * 32, [r // 4 for r in range(32)]
+    elif name == "prefill_shared_image_b32":
+        rng = np.random.default_rng(np.random.PCG64(2203 + 7919))
+        shared, H, Hkv, seed = _s(2880, shrink), 32, 8, 2203
+        prefix = [shared + _s(int(rng.integers(0, 601)), shrink) for _ in range(32)]
+        new = [int(rng.integers(6, 41)) for _ in range(32)]
+        group = [r // 8 for r in range(32)]
+    else:
+        raise KeyError(name)
+    return build_workload(name, "causal", "bf16", seed, num_q_heads=H, num_kv_heads=Hkv, head_dim=128, page_size=16,
+                          prefix_lens=prefix, new_lens=new, share_group=group, shared_len=[shared] * len(prefix),
+                          spare_pages=8)
+
+
+PREFILL_SHARED_CONFIGS = ("prefill_shared_video_b8_n12", "prefill_shared_video_b32_n4", "prefill_shared_image_b32")
 SUFFIX_CONFIGS = ("suffix_b1_16k_n36", "suffix_b8_16k_n36", "suffix_b8_16k_n4", "suffix_b32_4k_n36")
 DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k", "decode_b1_16k", "decode_b1_128k")
 DECODE_SHARED_CONFIGS = ("decode_shared_video_b8", "decode_shared_video_b32", "decode_shared_image_b32")

@@ -53,6 +53,35 @@ int main(void)
     }
 
     {
+        /* two requests with the same four leading pages (64 cached tokens) and few new tokens: one sharing group */
+        const int32_t pt[16] = {5, 6, 7, 8, 9, -1, -1, -1, 5, 6, 7, 8, 10, -1, -1, -1};
+        const int32_t prefix[2] = {64, 64}, new_lens[2] = {3, 2}, cu[3] = {0, 3, 5};
+        int32_t shared_len[2], g_pt[8], g_prefix[1], g_new[1], g_cu[2], own_pt[16], own_prefix[2];
+        emm_prefill_shared_plan plan;
+        emm_batch small = b;
+        small.total_new_tokens = 5;
+        small.max_new_len = 3;
+        memset(&plan, 0, sizeof plan);
+        plan.req_shared_len = shared_len;
+        plan.group_page_table = g_pt;
+        plan.group_prefix_lens = g_prefix;
+        plan.group_new_lens = g_new;
+        plan.group_cu_new_lens = g_cu;
+        plan.own_page_table = own_pt;
+        plan.own_prefix_lens = own_prefix;
+        small.num_q_heads = 256;                                /* 64 query heads per KV head: 192 and 128 rows fill two tiles either way */
+        CHECK(emm_prefill_shared_plan_host(&small, pt, prefix, new_lens, cu, 64, 0, &plan) == EMM_OK && plan.num_groups == 0);
+        small.num_q_heads = 28;                                 /* 21 and 14 rows: two tiles apart, one together */
+        CHECK(emm_prefill_shared_plan_host(&small, pt, prefix, new_lens, cu, 64, 0, &plan) == EMM_OK);
+        CHECK(plan.num_groups == 1 && shared_len[0] == 64 && shared_len[1] == 64 && g_prefix[0] == 64 && g_new[0] == 5);
+        CHECK(own_prefix[0] == 0 && own_pt[0] == 9 && own_pt[8] == 10 && own_pt[4] == -1);
+        CHECK(plan.groups.num_reqs == 1 && plan.own.num_reqs == 2 && plan.groups.max_new_len == 5);
+        CHECK(emm_prefill_attn_shared_workspace_size(&plan.groups, &plan.own, &bytes) == EMM_OK && bytes > 0);
+        CHECK(emm_prefill_attn_shared(&plan.groups, &plan.own, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) == EMM_ERR_NULL);
+        CHECK(emm_prefill_shared_plan_host(&small, pt, prefix, new_lens, cu, 64, -1, &plan) == EMM_OK && plan.num_groups == 0);
+    }
+
+    {
         uint8_t digest[32];
         int64_t ids[48], tokens[60];
         int32_t row[8], prefix_len = -1;
