@@ -22,7 +22,8 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # published dense bf16 MFMA figure of MI355X 
 HBM_PEAK_GBS = 8000.0
 
 
-W_PREFILL_SHARED = ("prefill_shared_video_b8_n12", "prefill_shared_video_b32_n4", "prefill_shared_image_b32")
+W_PREFILL_SHARED = ("prefill_shared_video_b8_n12", "prefill_shared_video_b32_n4", "prefill_shared_video_b64_n4",
+                    "prefill_shared_image_b32")
 
 
 def log(*a):

@@ -182,15 +182,18 @@ emm_status emm_decode_attn_static(const emm_batch *batch, const void *q, const v
  * default, EMM_PREFILL_SHARED_MIN_SAVED_KEY_TILES, measured on MI355X on batches of 8 .. 32 requests).  It writes,
  * into host arrays the caller provides, what the two passes need:
  *   req_shared_len    [B]                        tokens of request r done in its group's pass; 0: in no group
- *   group_page_table  [B / 2][max_pages_per_req] page-table row of each group's first member
+ *   group_page_table  [B / 2][max_pages_per_req] page-table row of each group's first member (*)
  *   group_prefix_lens, group_new_lens [B / 2]    shared length; new tokens of all members together
  *   group_cu_new_lens [B / 2 + 1]                first packed row of each group (members are consecutive)
- *   own_page_table    [B][max_pages_per_req]     each request's row moved left by the pages of its shared part
+ *   own_page_table    [B][max_pages_per_req]     each request's row moved left by the pages of its shared part (*)
  *   own_prefix_lens   [B]                        prefix_lens[r] - req_shared_len[r]
+ * (*) the sizes are what the caller provides; the rows are written packed, as narrow as what they hold allows, with
+ * the row stride that the descriptor states (groups.max_pages_per_req, own.max_pages_per_req <= the batch's): the
+ * launches size their grids, and decide whether anything is cut along the keys, from that width.
  * and fills the scalar fields of two descriptors, `groups` (one "request" per group) and `own` (the batch itself
  * with the moved page table), whose four array pointers it leaves NULL: the caller copies the arrays to the
  * device and sets them (own.new_lens and own.cu_new_lens are the batch's).  num_groups == 0: nothing to gain, use
- * emm_prefill_attn (req_shared_len is then all zero and `own` is the batch as it was).  rows_tiles_plain /
+ * emm_prefill_attn (req_shared_len is then all zero and `own` is the batch itself).  rows_tiles_plain /
  * rows_tiles_shared: 256-row tiles per KV head over the shared keys without and with the groups; they and the two
  * key-tile counts describe the grouping that was found, also when it was then given up as not worth it.
  *

@@ -296,6 +296,9 @@ def emm_prefill_shared_plan_host(batch: emm_batch, page_table: np.ndarray, prefi
     _check(load().emm_prefill_shared_plan_host(ctypes.byref(batch), *[a.ctypes.data_as(i32p) for a in ins], min_shared_tokens,
                                                min_saved_key_tiles, ctypes.byref(plan)), "emm_prefill_shared_plan_host")
     NG = int(plan.num_groups)
+    wg, wo = max(int(plan.groups.max_pages_per_req), 1), max(int(plan.own.max_pages_per_req), 1)
+    arr["group_page_table"] = arr["group_page_table"].reshape(-1)[:half * wg].reshape(half, wg)
+    arr["own_page_table"] = arr["own_page_table"].reshape(-1)[:max(B_, 1) * wo].reshape(max(B_, 1), wo)
     out = {"num_groups": NG, "rows_tiles_plain": int(plan.rows_tiles_plain), "rows_tiles_shared": int(plan.rows_tiles_shared),
            "key_tiles_plain": int(plan.key_tiles_plain), "key_tiles_shared": int(plan.key_tiles_shared),
            "req_shared_len": arr["req_shared_len"][:B_], "group_page_table": arr["group_page_table"][:max(NG, 1)],

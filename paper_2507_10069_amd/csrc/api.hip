@@ -458,6 +458,7 @@ extern "C" emm_status emm_prefill_shared_plan_host(const emm_batch* b, const int
     };
     int NG = 0;
     int64_t plain = 0, shared_tiles = 0;
+    std::vector<int> group_first(static_cast<size_t>(B) / 2 + 1);
     for (int r = 0; r < B; ++r) plan->req_shared_len[r] = 0;
     for (int i = 0; i < B;) {
         int n = 1;
@@ -481,7 +482,7 @@ extern "C" emm_status emm_prefill_shared_plan_host(const emm_batch* b, const int
         const bool pays = n >= 2 && tiles(sum_new) < before;
         if (pays) {
             for (int r = i; r < i + n; ++r) plan->req_shared_len[r] = static_cast<int32_t>(S);
-            std::copy(pt + static_cast<int64_t>(i) * mp, pt + static_cast<int64_t>(i + 1) * mp, plan->group_page_table + NG * mp);
+            group_first[NG] = i;
             plan->group_prefix_lens[NG] = static_cast<int32_t>(S);
             plan->group_new_lens[NG] = static_cast<int32_t>(sum_new);
             plan->group_cu_new_lens[NG] = cu[i];
@@ -513,14 +514,30 @@ extern "C" emm_status emm_prefill_shared_plan_host(const emm_batch* b, const int
         for (int r = 0; r < B; ++r) plan->req_shared_len[r] = 0;
     }
     plan->group_cu_new_lens[NG] = b->total_new_tokens;
-    // every request's own part: its page-table row moved left by the pages of the shared part
+    // The two page tables are packed as narrow as what they hold allows (the descriptors' max_pages_per_req is their
+    // row stride): the launches size their grids and decide about cutting along the keys from that width.
+    //   groups: the shared pages of the longest shared part
+    int64_t wg = 1;
+    for (int g = 0; g < NG; ++g) wg = std::max<int64_t>(wg, plan->group_prefix_lens[g] / ps);
+    wg = std::min(wg, std::max<int64_t>(mp, 1));
+    for (int g = 0; g < NG; ++g) {
+        const int32_t* src = pt + static_cast<int64_t>(group_first[g]) * mp;
+        for (int64_t p = 0; p < wg; ++p) plan->group_page_table[g * wg + p] = p < mp ? src[p] : -1;
+    }
+    plan->groups.max_pages_per_req = static_cast<int32_t>(wg);
+    //   own: every request's row moved left by the pages of its shared part, as wide as the longest own part
+    int64_t wo = 1;
+    for (int r = 0; r < B; ++r)
+        wo = std::max<int64_t>(wo, (static_cast<int64_t>(prefix[r]) - plan->req_shared_len[r] + new_lens[r] + ps - 1) / ps);
+    wo = std::min(wo, std::max<int64_t>(mp, 1));
     for (int r = 0; r < B; ++r) {
         const int64_t skip = plan->req_shared_len[r] / ps;
-        int32_t* row = plan->own_page_table + static_cast<int64_t>(r) * mp;
+        int32_t* row = plan->own_page_table + static_cast<int64_t>(r) * wo;
         const int32_t* src = pt + static_cast<int64_t>(r) * mp;
-        for (int64_t p = 0; p < mp; ++p) row[p] = p + skip < mp ? src[p + skip] : -1;
+        for (int64_t p = 0; p < wo; ++p) row[p] = p + skip < mp ? src[p + skip] : -1;
         plan->own_prefix_lens[r] = prefix[r] - plan->req_shared_len[r];
     }
+    plan->own.max_pages_per_req = static_cast<int32_t>(wo);
     plan->num_groups = NG;
     plan->groups.num_reqs = NG;
     plan->rows_tiles_plain = plain;

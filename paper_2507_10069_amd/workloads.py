@@ -380,6 +380,7 @@ def prefill_shared_config(name: str, shrink: int = 1) -> Workload:
     that single requests leave mostly empty.
       prefill_shared_video_b8_n12   8 requests about one video: 16384 shared tokens, 12 new tokens each, 28/4 heads
       prefill_shared_video_b32_n4   8 videos with 4 requests each, 16384 shared tokens, 4 new tokens each, 28/4 heads
+      prefill_shared_video_b64_n4   the same 8 videos with 8 requests each
       prefill_shared_image_b32      32 requests in 4 groups of 8 sharing 2880 tokens (system prompt + image), then
                                     0..600 cached tokens of their own and 6..40 new ones, 32/8 heads"""
     if name == "prefill_shared_video_b8_n12":
@@ -388,6 +389,9 @@ def prefill_shared_config(name: str, shrink: int = 1) -> Workload:
     elif name == "prefill_shared_video_b32_n4":
         shared, H, Hkv, seed = _s(16384, shrink), 28, 4, 2202
         prefix, new, group = [shared] * 32, [4] * 32, [r // 4 for r in range(32)]
+    elif name == "prefill_shared_video_b64_n4":
+        shared, H, Hkv, seed = _s(16384, shrink), 28, 4, 2204
+        prefix, new, group = [shared] * 64, [4] * 64, [r // 8 for r in range(64)]
     elif name == "prefill_shared_image_b32":
         rng = np.random.default_rng(np.random.PCG64(2203 + 7919))
         shared, H, Hkv, seed = _s(2880, shrink), 32, 8, 2203
@@ -401,7 +405,8 @@ def prefill_shared_config(name: str, shrink: int = 1) -> Workload:
                           spare_pages=8)
 
 
-PREFILL_SHARED_CONFIGS = ("prefill_shared_video_b8_n12", "prefill_shared_video_b32_n4", "prefill_shared_image_b32")
+PREFILL_SHARED_CONFIGS = ("prefill_shared_video_b8_n12", "prefill_shared_video_b32_n4", "prefill_shared_video_b64_n4",
+                          "prefill_shared_image_b32")
 SUFFIX_CONFIGS = ("suffix_b1_16k_n36", "suffix_b8_16k_n36", "suffix_b8_16k_n4", "suffix_b32_4k_n36")
 DECODE_CONFIGS = ("decode_video_b8", "decode_mixed_b32", "decode_b64_8k", "decode_b1_16k", "decode_b1_128k")
 DECODE_SHARED_CONFIGS = ("decode_shared_video_b8", "decode_shared_video_b32", "decode_shared_image_b32")

@@ -74,7 +74,8 @@ int main(void)
         small.num_q_heads = 28;                                 /* 21 and 14 rows: two tiles apart, one together */
         CHECK(emm_prefill_shared_plan_host(&small, pt, prefix, new_lens, cu, 64, 0, &plan) == EMM_OK);
         CHECK(plan.num_groups == 1 && shared_len[0] == 64 && shared_len[1] == 64 && g_prefix[0] == 64 && g_new[0] == 5);
-        CHECK(own_prefix[0] == 0 && own_pt[0] == 9 && own_pt[8] == 10 && own_pt[4] == -1);
+        CHECK(own_prefix[0] == 0 && plan.own.max_pages_per_req == 1 && own_pt[0] == 9 && own_pt[1] == 10);   /* packed rows */
+        CHECK(plan.groups.max_pages_per_req == 4 && g_pt[0] == 5 && g_pt[3] == 8);
         CHECK(plan.groups.num_reqs == 1 && plan.own.num_reqs == 2 && plan.groups.max_new_len == 5);
         CHECK(emm_prefill_attn_shared_workspace_size(&plan.groups, &plan.own, &bytes) == EMM_OK && bytes > 0);
         CHECK(emm_prefill_attn_shared(&plan.groups, &plan.own, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) == EMM_ERR_NULL);

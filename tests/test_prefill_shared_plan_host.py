@@ -42,6 +42,11 @@ def _check_plan(wl, p):
     S = p["req_shared_len"]
     NG = p["num_groups"]
     assert p["groups"].num_reqs == NG and p["own"].num_reqs == Bn
+    # the tables are packed as narrow as their contents allow
+    own_pages = [-(-(int(wl.prefix_lens[r]) - int(S[r]) + int(wl.new_lens[r])) // ps) for r in range(Bn)]
+    assert p["own"].max_pages_per_req == max(1, max(own_pages)) == p["own_page_table"].shape[1]
+    if NG:
+        assert p["groups"].max_pages_per_req == max(p["group_prefix_lens"][:NG]) // ps == p["group_page_table"].shape[1]
     assert p["groups"].total_new_tokens == wl.total_new_tokens == p["own"].total_new_tokens
     # members of a group are consecutive requests with the same shared length
     covered = np.zeros(Bn, bool)
@@ -83,9 +88,10 @@ def test_named_workloads_are_grouped_as_they_were_built(name):
     wl = W.prefill_shared_config(name, 8)
     p = _plan(wl)
     _check_plan(wl, p)
-    want = {"prefill_shared_video_b8_n12": 1, "prefill_shared_video_b32_n4": 8, "prefill_shared_image_b32": 4}[name]
+    want = {"prefill_shared_video_b8_n12": 1, "prefill_shared_video_b32_n4": 8, "prefill_shared_video_b64_n4": 8,
+            "prefill_shared_image_b32": 4}[name]
     assert p["num_groups"] == want
-    shared = {"prefill_shared_video_b8_n12": 16384 // 8, "prefill_shared_video_b32_n4": 16384 // 8, "prefill_shared_image_b32": 2880 // 8}[name]
+    shared = 2880 // 8 if "image" in name else 16384 // 8
     assert (p["req_shared_len"] == shared // 64 * 64).all()
 
 
