@@ -48,7 +48,7 @@ constexpr int BK = 32;                           // keys per tile: two 16-key bl
 constexpr int TILE_BYTES = BK * D * 2;           // one K or V tile in LDS: 32 rows of 256 bytes
 constexpr int NSLOT = 3;                         // ring depth; tile i of a piece lives in slot i % NSLOT
 constexpr int AHEAD = 2;                         // tiles in flight beyond the one being computed
-constexpr int MIN_TILES_PER_PIECE = 4, MAX_TILES_PER_PIECE = 60;   // 60 + AHEAD page ids fit the 64 lanes
+constexpr int MIN_TILES_PER_PIECE = 4, MAX_TILES_PER_PIECE = 124;  // 124 + AHEAD page ids fit two registers of 64 lanes
 constexpr int WORKGROUPS_PER_ROUND = 3 * 256;     // three workgroups on each of 256 CUs
 constexpr int OVERHEAD_TILES = 4;                // start and finish of a workgroup, in tile times
 constexpr int MAX_ROWS = 32;                     // query rows of a shared-prefix unit: the MFMA's columns
@@ -107,12 +107,16 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int t_off = (SHARED && !unit_mode) ? max(sv.req_shared_len[r], 0) / BK : 0;   // tiles a unit computes for this request
     const int t_begin = t_off + piece * S.tiles_per_piece;
     // lane k of a wave holds where in the pool the 16-key block lies that this wave fetches for tile t_begin + k
-    // (a piece has at most 60 tiles and fetches run two tiles ahead, so 64 lanes cover it).  Asked for before the lengths are
+    // and in a second register for tile t_begin + 64 + k (a piece has at most 124 tiles and fetches run two tiles
+    // ahead, so two registers cover it).  Asked for before the lengths are
     // known, so that the two loads overlap: entries past the request's pages are read (the row has
     // max_pages of them) and whatever they hold is forced into the pool; those keys are masked.
     const int32_t* __restrict__ pt = b.page_table + (long long)r * b.max_pages;
     const int blk16 = (t_begin + lane) * 2 + (wave >> 1);                 // logical 16-key block of the request
     const int pg_raw = b.max_pages > 0 ? pt[min(blk16 >> b.page_shift, b.max_pages - 1)] : 0;
+    const bool long_piece = S.tiles_per_piece + AHEAD > 64;  // the same for the whole grid
+    const int blk16_hi = blk16 + 128;
+    const int pg_raw_hi = (long_piece && b.max_pages > 0) ? pt[min(blk16_hi >> b.page_shift, b.max_pages - 1)] : 0;
     int kv_len, n_pieces, n_rows;
     bool direct;                                             // one piece and no unit: this workgroup writes the output
     if (!unit_mode) {
@@ -136,6 +140,8 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     // in units of 4096 bytes (one block of one KV head): (page, KV head, block within the page)
     const int pg_vec = ((min(max(pg_raw, 0), b.num_pages - 1) * b.num_kv_heads + kvh) << b.page_shift) +
                        (blk16 & ((1 << b.page_shift) - 1));
+    const int pg_vec_hi = ((min(max(pg_raw_hi, 0), b.num_pages - 1) * b.num_kv_heads + kvh) << b.page_shift) +
+                          (blk16_hi & ((1 << b.page_shift) - 1));
     const int l32 = lane & 31, h32 = lane >> 5;
     const int limit = kv_len - 1;                            // last visible key (the query's own slot if causal)
     const int n_clear = kv_len / BK;                         // tiles 0 .. n_clear-1 need no mask
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     const int ld_lds = wave * 8 * 256;
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
     auto load_tile = [&](int i, int slot) {                  // tile t_begin + i into ring slot `slot`
-        const long long off = (long long)__builtin_amdgcn_readlane(pg_vec, i) * 4096;
+        const long long off = (long long)__builtin_amdgcn_readlane(i < 64 ? pg_vec : pg_vec_hi, i & 63) * 4096;
         lds_dma16(kcb + off, k_goff0, smem_base + slot * TILE_BYTES + ld_lds);
         lds_dma16(kcb + off, (k_goff0 ^ 64) + 2048, smem_base + slot * TILE_BYTES + ld_lds + 1024);
         lds_dma16(vcb + off, v_goff0, smem_base + V_SM + slot * TILE_BYTES + ld_lds);

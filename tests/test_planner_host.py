@@ -166,7 +166,7 @@ def test_argument_errors():
 @pytest.mark.parametrize("n_req,Hkv,G,max_pages", [(1, 4, 7, 1024), (8, 4, 7, 1152), (64, 4, 7, 512), (32, 8, 4, 290), (3, 1, 16, 40),
                                                    (200, 8, 1, 64), (1, 4, 7, 8192), (5, 2, 3, 1)])
 def test_decode_workspace_holds_the_pieces_of_the_longest_context(n_req, Hkv, G, max_pages):
-    """A decode batch's workspace is [pair][piece][16 rows][130 floats]; pieces are 4 .. 60 tiles of 32 keys, and
+    """A decode batch's workspace is [pair][piece][16 rows][130 floats]; pieces are 4 .. 124 tiles of 32 keys, and
     there must be enough of them for a context that fills the page-table row."""
     b = B.make_batch(num_reqs=n_req, num_q_heads=Hkv * G, num_kv_heads=Hkv, head_dim=128, page_size=16, num_pages=1 << 20,
                      max_pages_per_req=max_pages, total_new_tokens=n_req, max_new_len=1, dtype="bf16", softmax_scale=0.1)
@@ -175,7 +175,7 @@ def test_decode_workspace_holds_the_pieces_of_the_longest_context(n_req, Hkv, G,
     assert size % (n_req * Hkv * per_piece) == 0
     pieces = size // (n_req * Hkv * per_piece)
     tiles = -(-max_pages * 16 // 32)
-    assert -(-tiles // 60) <= pieces <= max(-(-tiles // 4), 1)
+    assert -(-tiles // 124) <= pieces <= max(-(-tiles // 4), 1)
     # hints can only shrink it; a hint larger than the table changes nothing
     small = B.make_shared_prefix(0, planned_tiles=n_req * 4, max_own_tiles=4)
     assert B.emm_decode_attn_shared_workspace_size(b, small) <= size
