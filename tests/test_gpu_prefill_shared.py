@@ -96,6 +96,30 @@ def test_page_sizes(ps):
     print("   errors (max, mean, lse):", _compare(wl, dw), flush=True)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_batches_elementwise(seed):
+    """Random groups, lengths, head counts and page sizes; requests outside any group and requests without new tokens
+    mixed in; a member whose cached part ends inside the group's shared pages."""
+    rng = np.random.default_rng(1000 + seed)
+    ps = int(rng.choice([16, 32, 64]))
+    H, Hkv = [(28, 4), (32, 8), (8, 8), (16, 2), (4, 1)][seed % 5]
+    n = int(rng.integers(3, 11))
+    group = sorted(int(g) for g in rng.integers(0, max(2, n // 2), size=n))
+    shared_of = {g: int(rng.integers(1, 24)) * 64 for g in set(group)}
+    shared = [shared_of[g] for g in group]
+    prefix = [s_ + int(rng.integers(0, 150)) for s_ in shared]
+    new = [int(rng.integers(1, 30)) for _ in range(n)]
+    if n > 4:
+        new[int(rng.integers(0, n))] = 0
+        k = int(rng.integers(0, n))
+        prefix[k] = int(rng.integers(shared[k] // 2, shared[k] + 1))
+    print("case seed %d: ps %d, heads %d/%d, groups %s, shared %s, prefix %s, new %s" % (seed, ps, H, Hkv, group, shared, prefix, new), flush=True)
+    wl = _case(prefix, new, group, shared, H=H, Hkv=Hkv, ps=ps, seed=2000 + seed)
+    dw, plan = _run_shared(wl)
+    print("   groups %d, shared lengths %s, errors (max, mean, lse):" % (plan["num_groups"], plan["req_shared_len"].tolist()),
+          _compare(wl, dw), flush=True)
+
+
 def test_a_batch_without_groups_equals_the_plain_path_bitwise():
     wl = _case([700, 64, 0], [20, 3, 45], None, None)
     dw, plan = _run_shared(wl)
