@@ -562,6 +562,17 @@ def main():
                             "new_tokens_per_s": w.total_new_tokens / (m * 1e-3)}
             log("workload %s: %s" % (name, others[name]))
             del d
+        for name in W.PREFILL_SHARED_CONFIGS:            # short suffixes over shared cached pages: plain call and the grouped one
+            w = W.prefill_shared_config(name)
+            d = B.DeviceWorkload(w)
+            m, am, sm = time_workload(d, 30, 5)
+            plan = d.plan_prefill_shared(min_saved_key_tiles=0)
+            ms_, ams, _ = time_workload(d, 30, 5, d.attention_prefill_shared)
+            others[name] = {"ms_per_step": m, "attention_ms": am, "scatter_ms": sm, "shared_attention_ms": ams,
+                            "sharing_groups": plan["num_groups"], "speedup_over_plain_attention": am / ams,
+                            "new_tokens_per_s": w.total_new_tokens / (min(m, ms_) * 1e-3)}
+            log("workload %s: %s" % (name, others[name]))
+            del d
         for name in W.DECODE_CONFIGS:
             w = W.decode_config(name)
             d = B.DeviceWorkload(w)

@@ -26,14 +26,16 @@
 //
 // Software pipeline.  The softmax arithmetic is placed inside the MFMA stream of the same wave:
 // the iteration for tile i computes S(i+1) = K(i+1) Q^T (16 MFMA) while the VALU turns S(i) into
-// P(i) = exp2(S(i) - m), then O += V(i)^T P(i) (16 MFMA) while the VALU takes the row maximum of
-// S(i+1); the body is written as 32 one-MFMA slices fenced by scheduling barriers, so the issue
-// order is the written one.  The row sums of P (of the bf16-rounded values, so that the normaliser
-// matches the numerator) are taken on the matrix pipe as well, with eight small 4x4x4 MFMAs per
-// tile: dot-product instructions on the VALU do not overlap with MFMAs.  The running maximum m may
-// lag the true maximum by up to 2^8 (it only has to keep exp2 in range); O and l are rescaled only
-// when a row exceeds that.  K and V tiles live in 4-deep rings in LDS, fetched two iterations ahead,
-// with one workgroup barrier per tile placed mid-iteration; the loop body exists in four copies
+// P(i) = exp2(S(i) c - mc), then O += V(i)^T P(i) (16 MFMA); the body is written as 32 one-MFMA slices
+// fenced by scheduling barriers, so the issue order is the written one.  The row sums of P (of the
+// bf16-rounded values, so that the normaliser matches the numerator) are taken on the matrix pipe as
+// well, with eight small 4x4x4 MFMAs per tile: dot-product instructions on the VALU do not overlap
+// with MFMAs.  mc is a per-row reference exponent, not the running maximum: it starts as the maximum of
+// the row's first tile and is raised, by whole powers of two, only when a tile's row sum shows that the
+// weights have grown large; the loop takes no row maxima.  A unit whose weights overflowed all the same
+// (l infinite at its end: every workgroup votes) is done again by a second, careful instantiation that
+// keeps the true running maximum.  K and V tiles live in 4-deep rings in LDS, fetched two iterations
+// ahead, with one workgroup barrier per tile placed mid-iteration; the loop body exists in four copies
 // (ring slot) so buffer offsets and register roles are compile-time constants.
 //
 // Work units left over after an XCD's full rounds of 32 are cut along the key axis and merged by
@@ -42,8 +44,9 @@
 //
 // Cost model (measured on gfx950): per MFMA of 32 cycles the SIMD's VALU issue port is taken ~13 cycles
 // by the MFMA itself, ~4.3 by each plain VALU instruction, ~8.6 by v_exp_f32, and ~5.6 per KiB of LDS
-// data returned; the loop needs fma + exp + 1/2 cvt + 1/2 max per MFMA plus the row sums, i.e. it is
-// bound by that port (about 49 cycles per MFMA), not by the matrix pipe.
+// data returned; per score the loop needs an fma, an exp and half a cvt, besides the row sums and address
+// arithmetic, and runs at about 44 cycles per MFMA.  What holds it there is power, not issue slots: with
+// all compute units busy the chip clocks at about 1.65 GHz, and instructions saved come back as clock.
 #include "attn_bf16_common.h"
 
 #include <algorithm>

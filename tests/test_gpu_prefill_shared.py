@@ -163,6 +163,41 @@ def test_without_lse_and_repeated_calls_are_deterministic():
     assert first.tobytes() == B.DeviceWorkload.to_numpy_bits(dw.out).tobytes()
 
 
+def test_the_three_steps_can_be_captured_in_a_hip_graph_and_replayed():
+    """emm_prefill_attn_shared only launches kernels on the given stream, so the step (scatter, then the grouped
+    attention) can be captured in a HIP graph; every replay, with eager work between the replays, reproduces the
+    eager result bit for bit."""
+    print("case graph capture", flush=True)
+    bits = B.DeviceWorkload.to_numpy_bits
+    wl = _case([2048 + 90, 2048, 2048 + 700, 300, 1024, 1024 + 33], [6, 9, 2, 40, 11, 7], [0, 0, 0, 1, 2, 2], [2048] * 3 + [0] + [1024] * 2,
+               seed=91)
+    eager, plan = _run_shared(wl)
+    assert plan["num_groups"] == 2
+    want_out, want_lse, want_k = bits(eager.out).tobytes(), eager.lse.cpu().numpy().tobytes(), bits(eager.k_cache).tobytes()
+    dw = B.DeviceWorkload(wl)
+    dw.plan_prefill_shared(min_saved_key_tiles=0)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        dw.scatter()
+        dw.attention_prefill_shared()                    # warm up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            dw.scatter()
+            dw.attention_prefill_shared()
+    for replay in range(3):
+        dw.out.zero_()                                   # eager work and a synchronisation between the replays
+        dw.lse.zero_()
+        dw.prefill_shared["workspace"].fill_(0x5A)       # stale workspace contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert bits(dw.out).tobytes() == want_out, replay
+        assert dw.lse.cpu().numpy().tobytes() == want_lse, replay
+        assert bits(dw.k_cache).tobytes() == want_k, replay
+    _compare(wl, dw)
+
+
 def test_error_codes():
     wl = W.prefill_shared_config("prefill_shared_video_b8_n12", 16)
     dw = B.DeviceWorkload(wl)
