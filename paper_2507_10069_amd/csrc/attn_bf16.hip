@@ -840,8 +840,10 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
             pv_tile(R, pc);
             if (i + 1 >= n_clear) mask_tile(i + 1, s_nxt);
         };
-        // four tiles per trip, straight-line (a tile's ring slot is its position in the body), then up to
-        // three more; every wave runs n_tiles-1 iterations, one barrier each
+        // four tiles per trip, straight-line (a tile's ring slot is its position in the body); the loop is left
+        // wherever the tiles end (separate copies of the body for the last one to three iterations were 1.7 % slower
+        // on the mixed workload: more code, and the register allocator deals worse with seven copies than with
+        // four); every wave runs n_tiles-1 iterations, one barrier each
         // (iteration() takes the absolute tile number; the ring slot is the position relative to t_begin)
         int i = t_begin;
         const int t_end = t_begin + n_tiles;
@@ -854,17 +856,18 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
             if ((n_tiles - 1) & 1) rescale_to_max(sc[1]);
             else rescale_to_max(sc[0]);
         } else {
-        for (; i + 4 < t_end; i += 4) {
-            if (i + 6 - pg_base >= 64) refill_pages(i + 2);  // tiles i+2 .. i+6 are fetched in this trip
+        for (;;) {
+            if (i + 6 - pg_base >= 64) refill_pages(i + 2);  // tiles i+2 .. i+6 may be fetched in this trip
+            if (i + 1 >= t_end) break;
             iteration(i, std::integral_constant<int, 0>{});
+            if (i + 2 >= t_end) break;
             iteration(i + 1, std::integral_constant<int, 1>{});
+            if (i + 3 >= t_end) break;
             iteration(i + 2, std::integral_constant<int, 2>{});
+            if (i + 4 >= t_end) break;
             iteration(i + 3, std::integral_constant<int, 3>{});
+            i += 4;
         }
-        if (i + 5 - pg_base >= 64) refill_pages(i + 2);      // the leftover iterations fetch tiles i+2 .. i+5
-        if (i + 1 < t_end) iteration(i, std::integral_constant<int, 0>{});
-        if (i + 2 < t_end) iteration(i + 1, std::integral_constant<int, 1>{});
-        if (i + 3 < t_end) iteration(i + 2, std::integral_constant<int, 2>{});
         }
         // ---- tail: tile n-1
         bf16x8 pf[2][2];
