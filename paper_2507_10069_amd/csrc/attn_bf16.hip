@@ -60,6 +60,7 @@ using namespace bf16attn;
 
 constexpr int BR = 256;           // rows per workgroup
 constexpr int PF_DIST = 2;          // MFMA operands are read from LDS this many slices ahead of their use
+constexpr int K_STEPS_KEPT = 7;     // the K operand's read addresses of steps 1 .. this many are kept in registers over the main loop
 constexpr int SOFTMAX_SLICES = 28;  // of an iteration's 32 one-MFMA slices, the first this many carry the softmax arithmetic
 constexpr float LAG_LIMIT = 1048576.f;      // 2^20: a tile's row sum beyond this raises the row's reference exponent
 constexpr float OVERFLOW_LIMIT = 1.329228e36f;    // 2^120: a row sum at or beyond this (or NaN) at the end of a unit means
@@ -68,10 +69,12 @@ constexpr int VOTE_OFFSET = 2 * NBUF * KV_BYTES - 64;   // LDS bytes of the 8 wa
                                             // clear of the output staging area at their start
 constexpr int OUT_STRIDE = 272;     // bytes between output rows staged in LDS: 256 + 16, which spreads the banks
 
-// Inside the main loop, addresses derived from a per-lane base by one XOR or add are recomputed every
-// iteration: hoisted out of the loop as invariants they would cost a dozen registers the loop does not have.
-// Written as volatile assembly, which the optimiser neither hoists nor merges, they cost the one instruction
-// and no copy of the base.  IMM: an inline constant or 32-bit literal.
+// Addresses derived from a per-lane base by one XOR or add, written as volatile assembly, which the optimiser neither
+// hoists nor merges nor makes again where the value is used: what is computed before the main loop stays in a
+// register over it (the dozen addresses of the operand reads and tile fetches: the loop has the registers for them
+// since its last iterations and the last tile share the loop's code, and keeping them is 1.5 % faster than making
+// them again in every iteration), what is computed inside costs the one instruction.  IMM: an inline constant or
+// 32-bit literal.
 template <int IMM>
 __device__ inline int xor_here(int x)
 {
@@ -448,6 +451,7 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
     const int v_goff0 = r16 * 256 + ((ld_p ^ ((r16 & 3) << 2)) << 4);
     const unsigned char* __restrict__ kcb = (const unsigned char*)a.k_cache;
     const unsigned char* __restrict__ vcb = (const unsigned char*)a.v_cache;
+    const int k_goff1 = xor_add_here(k_goff0, 64, 2048), v_goff1 = add_here<1024>(v_goff0);
     const int n_blocks_valid = (ctx_len + 15) >> 4;          // 16-key blocks (4096 bytes per KV head in the pool)
     const int ld_lds = wave * 8 * 256;                       // LDS byte offset of this wave's rows in a tile
     const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
@@ -469,12 +473,12 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
     auto load_k = [&](int kt, int kbuf) {
         const unsigned char* src = kcb + slab_of(kt);
         lds_dma16(src, k_goff0, smem_base + kbuf * KV_BYTES + ld_lds);
-        lds_dma16(src, xor_add_here(k_goff0, 64, 2048), smem_base + kbuf * KV_BYTES + ld_lds + 1024);
+        lds_dma16(src, k_goff1, smem_base + kbuf * KV_BYTES + ld_lds + 1024);
     };
     auto load_v = [&](int kt, int vbuf) {
         const unsigned char* src = vcb + slab_of(kt);
         lds_dma16(src, v_goff0, smem_base + V_SM + vbuf * KV_BYTES + ld_lds);
-        lds_dma16(src, add_here<1024>(v_goff0), smem_base + V_SM + vbuf * KV_BYTES + ld_lds + 1024);
+        lds_dma16(src, v_goff1, smem_base + V_SM + vbuf * KV_BYTES + ld_lds + 1024);
     };
     // after this wave's loads of V tile kt have landed: zero the rows (keys) it fetched that lie past
     // the request's tokens.  Only the request's last tile can have such rows.
@@ -657,6 +661,11 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
         //   slices 16..23  O += V(i)^T P(i), block 0  + rest of the exp2 work (block 1)
         //   slices 24..31  O += V(i)^T P(i), block 1  + row sums of P(i) (slice 24), row maximum of S(i+1)
         // Operands are read from LDS PF_DIST slices ahead of their MFMA.
+        // read addresses of the operands, kept over the loop: the three further channel blocks of V, the K steps
+        const int v_rd_kept[4] = {v_rd0, xor_here<(1 << 6)>(v_rd0), xor_here<(2 << 6)>(v_rd0), xor_here<(3 << 6)>(v_rd0)};
+        int k_rd_kept[8];
+        k_rd_kept[0] = k_rd0;
+        static_for<1, 1 + K_STEPS_KEPT>([&](auto sc_) { constexpr int st = decltype(sc_)::value; k_rd_kept[st] = xor_here<(st << 5)>(k_rd0); });
         auto iteration = [&](int i, auto par) {
             constexpr int R = decltype(par)::value;
             // tile i+1 needs masking / may hold keys past the request's tokens (both wave-uniform, both rare)
@@ -723,13 +732,16 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
             int v_addr[4] = {v_rd0, 0, 0, 0};                // of the four channel blocks: made at first use, then kept
             auto read_k = [&](auto kc) -> bf16x8 {           // operand of QK slice k: step k/2, key block k%2
                 constexpr int k = decltype(kc)::value;
-                if constexpr ((k & 1) == 0) k_addr = xor_here<((k >> 1) << 5)>(k_rd0);
+                if constexpr ((k & 1) == 0) {
+                    if constexpr ((k >> 1) <= K_STEPS_KEPT) k_addr = k_rd_kept[k >> 1];
+                    else k_addr = xor_here<((k >> 1) << 5)>(k_rd0);
+                }
                 return *(const bf16x8*)(smem + ((R + 1) & 3) * KV_BYTES + (k & 1) * 32 * 256 + k_addr);
             };
             auto read_v = [&](auto kc) -> bf16x8 {           // operand of PV slice k: kb = k/8, s = (k/4)%2, nb = k%4
                 constexpr int k = decltype(kc)::value;
                 typedef short s16x4 __attribute__((ext_vector_type(4)));
-                if constexpr (k >= 1 && k < 4) v_addr[k] = xor_here<(k << 6)>(v_rd0);
+                if constexpr (k >= 1 && k < 4) v_addr[k] = v_rd_kept[k];
                 const unsigned char* src = smem + R * KV_BYTES + (32 * (k >> 3) + 16 * ((k >> 2) & 1)) * 256 + v_addr[k & 3];
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src));
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(src + 4 * 256));
@@ -871,12 +883,10 @@ __device__ inline void attend_unit(const AttnArgs& a, const LaunchShape& L, cons
         }
         // ---- tail: tile n-1
         bf16x8 pf[2][2];
-        switch ((n_tiles - 1) & 3) {
-            case 0: exp_tile(sc[0], pf); pv_tile(0, pf); break;
-            case 1: exp_tile(sc[1], pf); pv_tile(1, pf); break;
-            case 2: exp_tile(sc[0], pf); pv_tile(2, pf); break;
-            default: exp_tile(sc[1], pf); pv_tile(3, pf); break;
-        }
+        const int last_slot = (n_tiles - 1) & 3;             // of the rings; the scores' place follows its parity
+        if (last_slot & 1) exp_tile(sc[1], pf);
+        else exp_tile(sc[0], pf);
+        pv_tile(last_slot, pf);
         }                                                    // active
     }
     // ---- every wave's fetches have landed and every wave is past its last read of the rings, which are free from
