@@ -135,15 +135,12 @@ def bench_timeline(workload, suffix=None, prefill_shared=None):
     if dw.workspace is None or dw.workspace.numel() < n_rec * 64:
         sys.exit("bench.py --timeline: the instrumented library was not loaded")
     dw.scatter()
-    for _ in range(20):
-        dw.attention()
-    torch.cuda.synchronize()
     dw.workspace[:n_rec * 64].zero_()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(3):                                  # the records of the last of three launches back to back
-        e0.record()
-        dw.attention()
+    for _ in range(200):                                # every launch overwrites the records: those of the last of 200
+        e0.record()                                     # launches back to back are read, with the clock where a
+        dw.attention()                                  # sustained run leaves it
         e1.record()
     torch.cuda.synchronize()
     rec = dw.workspace[:n_rec * 64].view(torch.int64).cpu().numpy().reshape(n_rec, 8)
