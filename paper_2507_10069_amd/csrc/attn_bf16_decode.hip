@@ -9,8 +9,9 @@
 //
 //   workgroup = one piece of one pair, 4 waves, 48 KB of LDS: three workgroups share a CU, so that two
 //               stream while the third starts up or writes its result.  All waves fetch the piece's
-//               tiles into LDS rings of 3 tiles (LDS-DMA, the prefill kernel's swizzled layout, 2 tiles
-//               in flight, one barrier per tile); wave w COMPUTES tiles w, w+4, ... of the piece, all
+//               tiles into LDS rings of 3 tiles (LDS-DMA, the prefill kernel's swizzled layout, a tile
+//               asked for two iterations before it is computed, every fetch landed at the iteration's
+//               one barrier: see the loop); wave w COMPUTES tiles w, w+4, ... of the piece, all
 //               waves holding the same G query rows (padded to the 32 columns of the MFMA).  The matrix
 //               pipe is mostly idle; the kernel is bound by the rate at which tiles arrive from HBM.
 //   merge 1   = the 4 waves' (maximum, row sum, accumulator) are combined through LDS;
@@ -47,7 +48,7 @@ constexpr int NT = NW * 64;
 constexpr int BK = 32;                           // keys per tile: two 16-key blocks (a page holds 1 to 16 blocks)
 constexpr int TILE_BYTES = BK * D * 2;           // one K or V tile in LDS: 32 rows of 256 bytes
 constexpr int NSLOT = 3;                         // ring depth; tile i of a piece lives in slot i % NSLOT
-constexpr int AHEAD = 2;                         // tiles in flight beyond the one being computed
+constexpr int AHEAD = 2;                         // a tile is asked for this many iterations before it is computed
 constexpr int MIN_TILES_PER_PIECE = 4, MAX_TILES_PER_PIECE = 124;  // 124 + AHEAD page ids fit two registers of 64 lanes
 constexpr int WORKGROUPS_PER_ROUND = 3 * 256;     // three workgroups on each of 256 CUs
 constexpr int OVERHEAD_TILES = 4;                // start and finish of a workgroup, in tile times
@@ -275,6 +276,13 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
     if (n_tiles > 0) {
         for (int i = 0; i < AHEAD; ++i) load_tile(i, i);     // past the piece's end: a clamped page, never read
         __builtin_amdgcn_s_waitcnt(0x0f70 | 4 * (AHEAD - 1));    // tile 0 has landed
+        // The query rows were asked for before the tiles and have landed with tile 0, but the compiler, which does
+        // not count the tile fetches, takes half of them to be still on their way and would wait for them where
+        // they are first used: inside the loop, in the middle of every tile this wave computes, with a wait that
+        // also covers every tile fetch in flight.  Using them here puts that wait in front of the loop, once, and
+        // leaves the waits of the loop to the one written there.
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(qf[s]));
         zero_v_tail(0, 0);
         patch_new_row(0, 0);
         __syncthreads();
@@ -283,7 +291,13 @@ __global__ __launch_bounds__(NT, 3) void attn_bf16_decode_kernel(AttnArgs a, Dec
             const int slot_next = slot == NSLOT - 1 ? 0 : slot + 1, slot_last = slot == 0 ? NSLOT - 1 : slot - 1;
             load_tile(i + AHEAD, slot_last);                 // the slot last read in iteration i-1
             if ((i & (NW - 1)) == wave) compute_tile(i, slot);
-            __builtin_amdgcn_s_waitcnt(0x0f70 | 4 * (AHEAD - 1));    // tile i+1 has landed
+            // Every fetch of this wave has landed before the barrier, tile i+2 as well as tile i+1: a workgroup
+            // thus has one tile on its way at a time, asked for at the start of an iteration and waited for at its
+            // end, three workgroups of a CU 48 KB between them.  Waiting for tile i+1 only (two tiles in flight,
+            // 96 KB per CU) is slower on everything that streams from HBM (decode_b64_8k 205 against 193 us; a
+            // fetch-only kernel shows the same: the rate falls as more is in flight), and so is waiting earlier,
+            // before or inside this wave's tile (decode_mixed_b32 49 and 53 against 44 us).
+            __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
             zero_v_tail(i + 1, slot_next);
             patch_new_row(i + 1, slot_next);
             __syncthreads();
