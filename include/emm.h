@@ -354,7 +354,9 @@ emm_status emm_validate_batch_host(const emm_batch *batch, const int32_t *host_p
  * scalar fields and a HOST copy of new_lens (diagnostics, sizing, tests; no GPU work).  The kernels deal the
  * (request, KV head) pairs to the chip's 8 XCDs and cut each pair's query rows into work units of 256 rows
  * (Section 3.3 prefill over cached prefixes; the decomposition is this library's).
- *   fan             each pair is dealt to this many XCDs (1 unless the batch has fewer than 8 pairs)
+ *   fan             each pair is dealt to this many XCDs: 1, or a power of two up to 8 when the batch has fewer than
+ *                   8 pairs, or when its requests differ in length and the number of KV heads is no multiple of 8
+ *                   (every XCD then gets the same share of every request)
  *   cutting         1: units left over after an XCD's full rounds of 32 may be cut along the keys or halved
  *   slots_per_xcd   workgroups per XCD that may hold a unit; grid = 8 * (slots_per_xcd + 31 if cutting)
  *   units[x]        work units of XCD x

@@ -150,8 +150,9 @@ constexpr size_t TIMELINE_BYTES = (size_t)TIMELINE_RECORDS * 64;
 constexpr size_t TIMELINE_BYTES = 0;
 #endif
 
-// With fewer than 8 (request, KV head) pairs some XCDs would get no work, so each pair is dealt to `fan`
-// XCDs: sub-pair pair * fan + j owns the row tiles j, j + fan, j + 2 fan, ...  "Pair" below means sub-pair.
+// With fewer than 8 (request, KV head) pairs some XCDs would get no work, and with requests of different lengths
+// and fewer than 8 KV heads the XCDs would get different amounts of it, so each pair is dealt to `fan` XCDs (see
+// launch_shape): sub-pair pair * fan + j owns the row tiles j, j + fan, j + 2 fan, ...  "Pair" below means sub-pair.
 struct LaunchShape {
     int n_row_tiles;        // row tiles of the longest request's sub-pairs
     int n_pairs;            // sub-pairs in the batch
@@ -1153,6 +1154,12 @@ static void launch_shape(const BatchView& b, bool has_workspace, LaunchShape& L,
     const long long n_real_pairs = (long long)b.num_reqs * b.num_kv_heads;
     int fan = 1;
     while (fan < NUM_XCD && n_real_pairs * fan * 2 <= NUM_XCD) fan *= 2;
+    // A request's KV heads go to consecutive XCDs; with fewer than 8 of them (or a number that 8 is no multiple
+    // of) a request reaches only some XCDs, and requests of different lengths then load the XCDs unevenly.
+    // Dealing every pair to `fan` XCDs with Hkv fan a multiple of 8 gives every XCD the same share of every
+    // request.  (A batch of equal requests is balanced without it.)
+    if ((long long)b.num_reqs * b.max_new_len != b.total_new_tokens)
+        while (fan < NUM_XCD && (b.num_kv_heads * fan) % NUM_XCD != 0) fan *= 2;
     const long long n_pairs = n_real_pairs * fan;                        // sub-pairs
     const long long n_row_tiles = (n_pair_tiles + fan - 1) / fan;        // per sub-pair
     const long long pairs_per_xcd = (n_pairs + NUM_XCD - 1) / NUM_XCD;
@@ -1202,14 +1209,14 @@ static void launch_shape(const BatchView& b, bool has_workspace, LaunchShape& L,
         L.ws_pieces = (int)most;
     }
     slots = pairs_per_xcd * n_row_tiles;                                 // one per row tile of the longest request, per pair
-    if (L.split && fan == 1) {
+    if (L.split) {
         // With cutting, workgroup j of an XCD takes the XCD's unit j, so the grid only has to cover the units there
         // are.  An XCD holds at most ceil(Hkv / 8) pairs of a request, and the row tiles of all requests number at
         // most T G / 256 + B: a batch of one long request and many short ones gets a grid of about its real size
         // instead of one with the longest request's row tiles for every pair (an empty workgroup still holds a
         // compute unit for about a microsecond).
-        const long long bound = (long long)((b.num_kv_heads + NUM_XCD - 1) / NUM_XCD) *
-                                ((long long)b.total_new_tokens * G / BR + b.num_reqs);
+        const long long bound = (long long)((b.num_kv_heads * fan + NUM_XCD - 1) / NUM_XCD) *
+                                ((long long)b.total_new_tokens * G / (BR * fan) + b.num_reqs);
         slots = slots < bound ? slots : bound;
     }
 }

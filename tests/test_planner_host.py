@@ -27,6 +27,9 @@ def _model(H, Hkv, new):
     fan = 1
     while fan < XCDS and pairs * fan * 2 <= XCDS:
         fan *= 2
+    if len(set(new)) > 1:                                      # requests of different lengths: every request on every XCD
+        while fan < XCDS and (Hkv * fan) % XCDS:
+            fan *= 2
     units = [0] * XCDS
     for p in range(pairs):
         tiles = -(-new[p // Hkv] * G // ROWS)
@@ -69,6 +72,10 @@ def test_named_workloads():
     p5 = B.emm_prefill_plan_host(_batch(32, 8, cfg5.new_lens.tolist()), cfg5.new_lens)
     want = sum(-(-int(n) * 4 // ROWS) for n in cfg5.new_lens)                           # every XCD holds one KV head of every request
     assert p5["units"] == [want] * 8 and p5["cutting"] == 1
+    cfg2 = W.config(2)                                           # requests of different lengths on 4 KV heads: each pair is
+    p2 = B.emm_prefill_plan_host(_batch(28, 4, cfg2.new_lens.tolist()), cfg2.new_lens)   # dealt to 2 XCDs, so that every XCD
+    assert p2["fan"] == 2                                        # gets half the row tiles of one KV head of every request
+    assert max(p2["units"]) - min(p2["units"]) <= len(cfg2.new_lens), p2["units"]
     no_ws = B.emm_prefill_plan_host(_batch(28, 4, [36]), [36], with_workspace=False)
     assert no_ws["cutting"] == 0 and no_ws["pieces"] == [1] * 8 and no_ws["grid"] == 8
 
