@@ -51,6 +51,7 @@ constexpr int NSLOT = 3;                         // ring depth; tile i of a piec
 constexpr int AHEAD = 2;                         // a tile is asked for this many iterations before it is computed
 constexpr int MIN_TILES_PER_PIECE = 4, MAX_TILES_PER_PIECE = 124;  // 124 + AHEAD page ids fit two registers of 64 lanes
 constexpr int WORKGROUPS_PER_ROUND = 3 * 256;     // three workgroups on each of 256 CUs
+constexpr int WORKGROUPS_PER_ROUND_ONE_REQUEST = 384;    // see decode_shape
 constexpr int OVERHEAD_TILES = 4;                // start and finish of a workgroup, in tile times
 constexpr int MAX_ROWS = 32;                     // query rows of a shared-prefix unit: the MFMA's columns
 static_assert(NW * MAX_G * REC_FLOATS * 4 <= 2 * NSLOT * TILE_BYTES, "the merge across waves reuses the tile rings");
@@ -492,6 +493,12 @@ __global__ __launch_bounds__(MERGE_GROUPS * D) void attn_bf16_decode_merge_kerne
 // units take work away `planned_tiles` is the amount that is left (32-key tiles per KV head, summed over
 // contexts).  Without them the host knows only the longest possible context (the width of the page table) and
 // plans for every context being that long.
+// A batch of ONE request has no short contexts beside long ones: its KV heads are all as long as each other, and
+// about as long as the table is wide.  HBM is then kept busy by half as many workgroups of twice the length, which
+// start, finish and are merged half as often: measured on a single context of 131072 tokens, 350 to 410
+// workgroups take 50.6-51.5 us, 570 take 55.1, 750 take 56.3 (and 256 take 56.0: too few).  Such a batch is
+// planned for rounds of 384.  (With several requests the same would help uniform batches by 1-4 % and cost a
+// ragged one 20 %, and the host cannot tell them apart.)
 DecodeShape decode_shape(const BatchView& b, const SharedPrefixView& sv = SharedPrefixView{})
 {
     DecodeShape S;
@@ -503,6 +510,7 @@ DecodeShape decode_shape(const BatchView& b, const SharedPrefixView& sv = Shared
                                  : sv.max_unit_tiles > 0 ? std::min<long long>(sv.max_unit_tiles, table_tiles) : table_tiles;
     const long long items = (long long)S.n_pairs + S.n_unit_pairs;
     auto pieces = [](long long tiles, int tpp) { return tiles > 0 ? (tiles + tpp - 1) / tpp : 1; };
+    const int per_round = (b.num_reqs == 1 && sv.num_units == 0) ? WORKGROUPS_PER_ROUND_ONE_REQUEST : WORKGROUPS_PER_ROUND;
     long long best_cost = -1;
     int best = MIN_TILES_PER_PIECE;
     for (int tpp = MIN_TILES_PER_PIECE; tpp <= MAX_TILES_PER_PIECE; ++tpp) {
@@ -511,7 +519,7 @@ DecodeShape decode_shape(const BatchView& b, const SharedPrefixView& sv = Shared
         const long long wgs = (sv.planned_tiles > 0 && sv.num_units > 0)
                                   ? std::min(grid, ((long long)sv.planned_tiles * b.num_kv_heads + tpp - 1) / tpp + items / 2)
                                   : grid;
-        const long long rounds = (wgs + WORKGROUPS_PER_ROUND - 1) / WORKGROUPS_PER_ROUND;
+        const long long rounds = (wgs + per_round - 1) / per_round;
         const long long cost = 128 * rounds * (tpp + OVERHEAD_TILES) + grid;         // in 1/128 tile times
         if (best_cost < 0 || cost <= best_cost) {            // ties: the longer piece, fewer records to merge
             best_cost = cost;
