@@ -188,3 +188,19 @@ def test_decode_workspace_holds_the_pieces_of_the_longest_context(n_req, Hkv, G,
     assert B.emm_decode_attn_shared_workspace_size(b, small) <= size
     wide = B.make_shared_prefix(0, planned_tiles=0, max_own_tiles=10 * tiles)
     assert B.emm_decode_attn_shared_workspace_size(b, wide) == size
+
+
+def test_decode_plan_of_a_single_request_uses_fewer_longer_pieces():
+    """One request cannot be ragged: its contexts are cut so that about 1.5 workgroups per compute unit (at most 384)
+    stream them, where a batch of several requests is planned for rounds of 768."""
+    per_piece = 16 * 130 * 4
+    def pieces(n_req, max_pages):
+        b = B.make_batch(num_reqs=n_req, num_q_heads=28, num_kv_heads=4, head_dim=128, page_size=16, num_pages=1 << 20,
+                         max_pages_per_req=max_pages, total_new_tokens=n_req, max_new_len=1, dtype="bf16", softmax_scale=0.1)
+        size = B.emm_prefill_attn_workspace_size(b)
+        assert size % (n_req * 4 * per_piece) == 0
+        return size // (n_req * 4 * per_piece)
+    one = pieces(1, 8192)                                       # 131072 tokens: 4096 tiles of 32 keys per KV head
+    assert 256 < 4 * one <= 384
+    two = pieces(2, 4096)                                       # the same number of tiles in two requests
+    assert 384 < 8 * two <= 768
